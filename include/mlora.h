@@ -1,0 +1,138 @@
+/*
+ * mlora.h -- C ABI of the MI355X (gfx950) BatchLoRA multi-adapter LoRA linear operator.
+ *
+ * The operator is the "BatchLoRA" training operator of the mLoRA paper
+ * (arXiv 2312.02515, section 3.3.1).  K independent LoRA fine-tuning tasks share
+ * one frozen weight W; their token matrices x_k are concatenated row-wise into
+ * X = (x_1^T ... x_K^T)^T, and
+ *
+ *   forward   (Eq. "forward"):      Y  = X W + rows_k( s_k x_k A_k B_k )
+ *   backward  (Eq. "grad_lora"):    dA_k = s_k x_k^T dy_k B_k^T
+ *                                   dB_k = s_k A_k^T x_k^T dy_k
+ *             (Eq. "grad_output"):  dX = dY W^T + rows_k( s_k dy_k B_k^T A_k^T )
+ *
+ * W receives no gradient (section 3.3.1).  The base products X W and dY W^T are
+ * launched once over the consolidated rows; the per-task LoRA terms are added at
+ * the rows recorded by the split positions `seg_offsets`, and dX is written once
+ * with the LoRA part already in it (the paper's "graph pruning": no zero-padded
+ * full-size intermediate exists).  The factor s_k (= alpha_k / r_k, computed by
+ * the caller) is this library's reading of the LoRA scaling, which the paper's
+ * equations leave out; s_k = 1 gives the paper's formulas verbatim.
+ *
+ * Shapes follow the paper's notation (Eq. 1):  W is [h, d] (h input features,
+ * d output features, Y = X W), A_k is [h, r_k], B_k is [r_k, d].  Every matrix is
+ * dense row-major with no padding between rows.
+ *
+ * Memory: the library owns nothing and allocates nothing.  Every pointer marked
+ * DEVICE is GPU memory allocated by the caller on the current HIP device; every
+ * pointer marked HOST is ordinary host memory that is read before the call
+ * returns (the caller may free or reuse it on return).  All work is enqueued on
+ * `hip_stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ * the calls return without waiting for it.
+ *
+ * Errors: every call validates its arguments first and returns a status; on any
+ * status other than MLORA_OK no kernel has been launched and no output has been
+ * touched (MLORA_ERR_HIP excepted: a launch failed midway).  Nothing aborts and
+ * no exception crosses this boundary.
+ */
+#ifndef MLORA_H
+#define MLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MLORA_MAX_ADAPTERS 64   /* K <= 64 per call */
+#define MLORA_MAX_RANK     128  /* 1 <= r_k <= 128  */
+
+typedef enum {
+  MLORA_OK            = 0,
+  MLORA_ERR_NULL      = 1,  /* a required pointer is NULL                                   */
+  MLORA_ERR_SHAPE     = 2,  /* T, h or d negative, h or d zero, K out of range, sizes too big */
+  MLORA_ERR_SEGMENTS  = 3,  /* seg_offsets not monotone or outside [0, T]                   */
+  MLORA_ERR_RANK      = 4,  /* a rank outside [1, MLORA_MAX_RANK]                           */
+  MLORA_ERR_DTYPE     = 5,  /* dtype is not one of mlora_dtype                              */
+  MLORA_ERR_WORKSPACE = 6,  /* workspace pointer NULL or workspace_bytes too small          */
+  MLORA_ERR_HIP       = 7   /* the HIP runtime reported an error (see mlora_last_hip_error) */
+} mlora_status;
+
+typedef enum {
+  MLORA_BF16 = 0,  /* X, W, A_k, B_k, dY, Y, dX stored as bfloat16; products accumulate in fp32 */
+  MLORA_F32  = 1   /* everything stored and accumulated in fp32                                */
+} mlora_dtype;
+
+/* One problem instance: the tasks T_1..T_K of section 3.3.1 over one shared W. */
+typedef struct {
+  int64_t T;                  /* total tokens (rows of X, Y, dY, dX); 0 is allowed (no-op)       */
+  int64_t h;                  /* input features  (columns of X, rows of W)                       */
+  int64_t d;                  /* output features (columns of W and Y)                            */
+  int32_t K;                  /* number of adapters, 0 <= K <= MLORA_MAX_ADAPTERS                */
+  int32_t dtype;              /* an mlora_dtype: element type of X, W, A_k, B_k, dY, Y, dX        */
+  const int64_t* seg_offsets; /* HOST, K+1 entries, 0 <= o_0 <= ... <= o_K <= T.  Task k owns rows
+                                 [o_k, o_{k+1}); an empty range is allowed.  Rows before o_0 and
+                                 from o_K on belong to no task and get the base term only.  May be
+                                 NULL when K == 0.                                               */
+  const int32_t* ranks;       /* HOST, K entries, r_k                                            */
+  const float*   scalings;    /* HOST, K entries, s_k                                            */
+  const void* const* A;       /* HOST array of K DEVICE pointers, A_k is [h, r_k]                */
+  const void* const* B;       /* HOST array of K DEVICE pointers, B_k is [r_k, d]                */
+  const void* W;              /* DEVICE, [h, d], frozen: never written                           */
+} mlora_problem;
+
+/* Size in bytes of the `saved` buffer that mlora_lora_fwd fills and mlora_lora_bwd reads
+ * (the intermediate s_k x_k A_k of the forward workflow, section 3.3.1, kept so that the
+ * backward pass does not recompute it).  Its layout is private to the library.
+ * Returns 0 if the problem is invalid. */
+size_t mlora_lora_saved_bytes(const mlora_problem* p);
+
+/* Size in bytes of the scratch `workspace` either call needs (the larger of the two).
+ * The workspace carries nothing from one call to the next.  Returns 0 if invalid. */
+size_t mlora_lora_workspace_bytes(const mlora_problem* p);
+
+/* Argument check only (no GPU needed): the status mlora_lora_fwd would return for `p`
+ * before looking at its other arguments. */
+mlora_status mlora_lora_validate(const mlora_problem* p);
+
+/* Forward, Eq. "forward":  Y[i,:] = X[i,:] W + s_k (X[i,:] A_k) B_k  for i in task k's rows.
+ *   X          DEVICE [T, h]  input, read only
+ *   Y          DEVICE [T, d]  output, fully overwritten; must not overlap any input
+ *   saved      DEVICE, mlora_lora_saved_bytes(p) bytes, output
+ *   workspace  DEVICE, at least mlora_lora_workspace_bytes(p) bytes, 256-byte aligned, scratch
+ */
+mlora_status mlora_lora_fwd(const mlora_problem* p, const void* X, void* Y, void* saved,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward, Eqs. "grad_lora" and "grad_output".
+ *   X, dY      DEVICE [T, h] / [T, d]  inputs, read only
+ *   saved      DEVICE, what mlora_lora_fwd wrote for the same problem and the same X, A_k, s_k
+ *   dX         DEVICE [T, h] output, fully overwritten, written once with the LoRA term
+ *              included; NULL skips it (first layer of a model)
+ *   dA, dB     HOST arrays of K DEVICE pointers to fp32 buffers [h, r_k] and [r_k, d]
+ *              (fp32 in both dtypes: they feed an optimiser or accumulate over micro-batches)
+ *   accumulate 0: dA_k, dB_k are overwritten (zeros for an empty segment);
+ *              1: the gradients are added to what the buffers hold
+ * Two tasks must not share a dA or dB buffer.  W is read, never written.
+ */
+mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* dY, const void* saved,
+                            void* dX, float* const* dA, float* const* dB, int accumulate,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Plain text for a status code; never NULL. */
+const char* mlora_status_string(mlora_status s);
+
+/* hipError_t (as int) of the last HIP failure seen by this thread's calls; 0 if none. */
+int mlora_last_hip_error(void);
+
+/* Selects which kernels the two entry points use, for testing and measurement:
+ *   0 (default) fastest applicable path (MFMA kernels when shapes allow, else generic),
+ *   1           generic kernels only.
+ * Returns the previous value.  Process-wide. */
+int mlora_set_kernel_path(int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLORA_H */

@@ -1,0 +1,166 @@
+"""Thin ctypes binding over the C ABI of libmlora.so (see include/mlora.h).
+
+Argument marshalling only: every arithmetic step runs in the library's HIP
+kernels.  PyTorch is used for device memory and streams.  There is no CPU
+fallback: if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmlora.so")
+
+MLORA_BF16 = 0
+MLORA_F32 = 1
+MLORA_MAX_ADAPTERS = 64
+MLORA_MAX_RANK = 128
+
+STATUS_NAMES = {0: "MLORA_OK", 1: "MLORA_ERR_NULL", 2: "MLORA_ERR_SHAPE", 3: "MLORA_ERR_SEGMENTS",
+                4: "MLORA_ERR_RANK", 5: "MLORA_ERR_DTYPE", 6: "MLORA_ERR_WORKSPACE", 7: "MLORA_ERR_HIP"}
+
+EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_validate", "mlora_lora_fwd",
+           "mlora_lora_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path"]
+
+
+class MloraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.mlora_status_string(status).decode()
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({msg}); hip error {lib.mlora_last_hip_error()}")
+
+
+class mlora_problem(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("h", ctypes.c_int64), ("d", ctypes.c_int64),
+                ("K", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("seg_offsets", ctypes.POINTER(ctypes.c_int64)),
+                ("ranks", ctypes.POINTER(ctypes.c_int32)),
+                ("scalings", ctypes.POINTER(ctypes.c_float)),
+                ("A", ctypes.POINTER(ctypes.c_void_p)),
+                ("B", ctypes.POINTER(ctypes.c_void_p)),
+                ("W", ctypes.c_void_p)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no fallback path.")
+    l = ctypes.CDLL(LIB_PATH)
+    pp = ctypes.POINTER(mlora_problem)
+    l.mlora_lora_saved_bytes.restype = ctypes.c_size_t
+    l.mlora_lora_saved_bytes.argtypes = [pp]
+    l.mlora_lora_workspace_bytes.restype = ctypes.c_size_t
+    l.mlora_lora_workspace_bytes.argtypes = [pp]
+    l.mlora_lora_validate.restype = ctypes.c_int
+    l.mlora_lora_validate.argtypes = [pp]
+    l.mlora_lora_fwd.restype = ctypes.c_int
+    l.mlora_lora_fwd.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                 ctypes.c_size_t, ctypes.c_void_p]
+    l.mlora_lora_bwd.restype = ctypes.c_int
+    l.mlora_lora_bwd.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                 ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    l.mlora_status_string.restype = ctypes.c_char_p
+    l.mlora_status_string.argtypes = [ctypes.c_int]
+    l.mlora_last_hip_error.restype = ctypes.c_int
+    l.mlora_last_hip_error.argtypes = []
+    l.mlora_set_kernel_path.restype = ctypes.c_int
+    l.mlora_set_kernel_path.argtypes = [ctypes.c_int]
+    return l
+
+
+lib = _load()
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.bfloat16:
+        return MLORA_BF16
+    if dt == torch.float32:
+        return MLORA_F32
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+class Problem:
+    """Host-side description of one call: owns the ctypes arrays the struct points to
+    and keeps the adapter tensors alive."""
+
+    def __init__(self, T: int, h: int, d: int, W: torch.Tensor, seg_offsets: Sequence[int], ranks: Sequence[int],
+                 scalings: Sequence[float], A: Sequence[torch.Tensor], B: Sequence[torch.Tensor]):
+        K = len(ranks)
+        self.T, self.h, self.d, self.K = int(T), int(h), int(d), K
+        self.ranks = [int(r) for r in ranks]
+        self.W, self.A, self.B = W, list(A), list(B)
+        self.torch_dtype = W.dtype
+        self._off = (ctypes.c_int64 * (K + 1))(*[int(o) for o in seg_offsets])
+        self._ranks = (ctypes.c_int32 * max(K, 1))(*self.ranks)
+        self._s = (ctypes.c_float * max(K, 1))(*[float(s) for s in scalings])
+        self._A = (ctypes.c_void_p * max(K, 1))(*[a.data_ptr() for a in A])
+        self._B = (ctypes.c_void_p * max(K, 1))(*[b.data_ptr() for b in B])
+        self.c = mlora_problem(T=self.T, h=self.h, d=self.d, K=K, dtype=_dtype_code(W.dtype),
+                               seg_offsets=ctypes.cast(self._off, ctypes.POINTER(ctypes.c_int64)),
+                               ranks=ctypes.cast(self._ranks, ctypes.POINTER(ctypes.c_int32)),
+                               scalings=ctypes.cast(self._s, ctypes.POINTER(ctypes.c_float)),
+                               A=ctypes.cast(self._A, ctypes.POINTER(ctypes.c_void_p)),
+                               B=ctypes.cast(self._B, ctypes.POINTER(ctypes.c_void_p)),
+                               W=W.data_ptr())
+
+    def saved_bytes(self) -> int:
+        return int(lib.mlora_lora_saved_bytes(ctypes.byref(self.c)))
+
+    def workspace_bytes(self) -> int:
+        return int(lib.mlora_lora_workspace_bytes(ctypes.byref(self.c)))
+
+    def validate(self) -> int:
+        return int(lib.mlora_lora_validate(ctypes.byref(self.c)))
+
+    def alloc_saved(self) -> torch.Tensor:
+        return torch.empty(self.saved_bytes(), dtype=torch.uint8, device=self.W.device)
+
+    def alloc_workspace(self) -> torch.Tensor:
+        return torch.empty(self.workspace_bytes(), dtype=torch.uint8, device=self.W.device)
+
+    def alloc_grads(self):
+        dA = [torch.empty((self.h, r), dtype=torch.float32, device=self.W.device) for r in self.ranks]
+        dB = [torch.empty((r, self.d), dtype=torch.float32, device=self.W.device) for r in self.ranks]
+        return dA, dB
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def mlora_lora_fwd(prob: Problem, X: torch.Tensor, Y: torch.Tensor, saved: torch.Tensor, workspace: torch.Tensor,
+                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Y = X W + rows_k(s_k x_k A_k B_k); fills `saved` for the backward call."""
+    st = lib.mlora_lora_fwd(ctypes.byref(prob.c), X.data_ptr(), Y.data_ptr(), saved.data_ptr(), workspace.data_ptr(),
+                            workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_fwd")
+
+
+def mlora_lora_bwd(prob: Problem, X: torch.Tensor, dY: torch.Tensor, saved: torch.Tensor,
+                   dX: Optional[torch.Tensor], dA: List[torch.Tensor], dB: List[torch.Tensor], accumulate: bool,
+                   workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """dX = dY W^T + rows_k(s_k dy_k B_k^T A_k^T); dA_k, dB_k as in Eq. grad_lora."""
+    K = prob.K
+    pa = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dA])
+    pb = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dB])
+    st = lib.mlora_lora_bwd(ctypes.byref(prob.c), X.data_ptr(), dY.data_ptr(), saved.data_ptr(),
+                            dX.data_ptr() if dX is not None else None,
+                            ctypes.cast(pa, ctypes.POINTER(ctypes.c_void_p)),
+                            ctypes.cast(pb, ctypes.POINTER(ctypes.c_void_p)), 1 if accumulate else 0,
+                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                            _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_bwd")
+
+
+def set_kernel_path(path: int) -> int:
+    return int(lib.mlora_set_kernel_path(int(path)))

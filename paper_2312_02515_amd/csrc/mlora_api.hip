@@ -1,0 +1,150 @@
+// C-ABI entry points of libmlora: argument validation, buffer layout, dispatch.
+// No kernel lives here.
+#include <atomic>
+
+#include "mlora_common.h"
+
+namespace mlora {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+std::atomic<int> g_kernel_path{0};
+
+mlora_status validate(const mlora_problem* p) {
+  if (p == nullptr) return MLORA_ERR_NULL;
+  if (p->dtype != MLORA_BF16 && p->dtype != MLORA_F32) return MLORA_ERR_DTYPE;
+  if (p->T < 0 || p->h <= 0 || p->d <= 0) return MLORA_ERR_SHAPE;
+  // row indices and feature indices are 32-bit inside the kernels
+  if (p->T > 0x7fffffffLL - 1024 || p->h > (1 << 24) || p->d > (1 << 24)) return MLORA_ERR_SHAPE;
+  if (p->K < 0 || p->K > kMaxK) return MLORA_ERR_SHAPE;
+  if (p->W == nullptr) return MLORA_ERR_NULL;
+  if (p->K > 0) {
+    if (!p->seg_offsets || !p->ranks || !p->scalings || !p->A || !p->B) return MLORA_ERR_NULL;
+    int64_t prev = 0;
+    for (int k = 0; k <= p->K; ++k) {
+      int64_t o = p->seg_offsets[k];
+      if (o < prev || o > p->T) return MLORA_ERR_SEGMENTS;
+      prev = o;
+    }
+    for (int k = 0; k < p->K; ++k) {
+      if (p->ranks[k] < 1 || p->ranks[k] > kMaxRank) return MLORA_ERR_RANK;
+    }
+    for (int k = 0; k < p->K; ++k) {
+      if (p->A[k] == nullptr || p->B[k] == nullptr) return MLORA_ERR_NULL;
+    }
+  }
+  return MLORA_OK;
+}
+
+size_t elem_size(const mlora_problem* p) { return p->dtype == MLORA_F32 ? 4 : 2; }
+
+// bytes of one [T, ldz] low-rank intermediate (Z in `saved`, G at the head of the workspace)
+size_t lowrank_bytes(const mlora_problem* p) {
+  return align_up((size_t)p->T * (size_t)lowrank_ld(p) * elem_size(p), 256);
+}
+
+void fill_ctx(const mlora_problem* p, void* stream, CallCtx* c) {
+  c->T = (int)p->T;
+  c->h = (int)p->h;
+  c->d = (int)p->d;
+  c->K = p->K;
+  c->ldz = lowrank_ld(p);
+  c->dtype = p->dtype;
+  c->W = p->W;
+  c->stream = static_cast<hipStream_t>(stream);
+  c->st.K = p->K;
+  for (int k = 0; k < kMaxK; ++k) {
+    bool live = k < p->K;
+    c->st.off[k] = live ? (int)p->seg_offsets[k] : 0;
+    c->st.rank[k] = live ? p->ranks[k] : 0;
+    c->st.s[k] = live ? p->scalings[k] : 0.f;
+    c->A.p[k] = live ? p->A[k] : nullptr;
+    c->B.p[k] = live ? p->B[k] : nullptr;
+  }
+  c->st.off[kMaxK] = 0;
+  if (p->K > 0) {
+    for (int k = p->K; k <= kMaxK; ++k) c->st.off[k] = (int)p->seg_offsets[p->K];
+  }
+}
+
+mlora_status hip_status(hipError_t e) {
+  if (e == hipSuccess) return MLORA_OK;
+  g_last_hip_error = (int)e;
+  return MLORA_ERR_HIP;
+}
+
+}  // namespace
+}  // namespace mlora
+
+using namespace mlora;
+
+extern "C" {
+
+mlora_status mlora_lora_validate(const mlora_problem* p) { return validate(p); }
+
+size_t mlora_lora_saved_bytes(const mlora_problem* p) {
+  if (validate(p) != MLORA_OK) return 0;
+  size_t b = lowrank_bytes(p);
+  return b ? b : 256;
+}
+
+size_t mlora_lora_workspace_bytes(const mlora_problem* p) {
+  if (validate(p) != MLORA_OK) return 0;
+  size_t b = lowrank_bytes(p);  // G
+  return b ? b : 256;
+}
+
+mlora_status mlora_lora_fwd(const mlora_problem* p, const void* X, void* Y, void* saved, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  mlora_status st = validate(p);
+  if (st != MLORA_OK) return st;
+  if (p->T == 0) return MLORA_OK;
+  if (X == nullptr || Y == nullptr || saved == nullptr) return MLORA_ERR_NULL;
+  if (workspace == nullptr || workspace_bytes < mlora_lora_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
+  CallCtx c;
+  fill_ctx(p, hip_stream, &c);
+  return hip_status(generic_fwd(c, X, Y, saved));
+}
+
+mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* dY, const void* saved, void* dX,
+                            float* const* dA, float* const* dB, int accumulate, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  mlora_status st = validate(p);
+  if (st != MLORA_OK) return st;
+  if (X == nullptr || dY == nullptr || saved == nullptr) return MLORA_ERR_NULL;
+  if (p->K > 0) {
+    if (dA == nullptr || dB == nullptr) return MLORA_ERR_NULL;
+    for (int k = 0; k < p->K; ++k)
+      if (dA[k] == nullptr || dB[k] == nullptr) return MLORA_ERR_NULL;
+  }
+  if (workspace == nullptr || workspace_bytes < mlora_lora_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
+  CallCtx c;
+  fill_ctx(p, hip_stream, &c);
+  OutTable ta, tb;
+  for (int k = 0; k < kMaxK; ++k) {
+    ta.p[k] = k < p->K ? dA[k] : nullptr;
+    tb.p[k] = k < p->K ? dB[k] : nullptr;
+  }
+  if (p->T == 0 && accumulate) return MLORA_OK;
+  return hip_status(generic_bwd(c, X, dY, saved, dX, ta, tb, accumulate ? 1 : 0, workspace));
+}
+
+const char* mlora_status_string(mlora_status s) {
+  switch (s) {
+    case MLORA_OK: return "ok";
+    case MLORA_ERR_NULL: return "a required pointer is NULL";
+    case MLORA_ERR_SHAPE: return "bad shape (T, h, d or K out of range)";
+    case MLORA_ERR_SEGMENTS: return "segment offsets not monotone within [0, T]";
+    case MLORA_ERR_RANK: return "adapter rank out of range";
+    case MLORA_ERR_DTYPE: return "unknown dtype";
+    case MLORA_ERR_WORKSPACE: return "workspace missing or too small";
+    case MLORA_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int mlora_last_hip_error(void) { return g_last_hip_error; }
+
+int mlora_set_kernel_path(int path) { return g_kernel_path.exchange(path); }
+
+}  // extern "C"

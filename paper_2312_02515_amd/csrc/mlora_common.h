@@ -1,0 +1,78 @@
+// Shared declarations of the HIP side of libmlora (gfx950 only).
+// Notation follows section 3.3.1 of the mLoRA paper: X [T,h], W [h,d], A_k [h,r_k],
+// B_k [r_k,d]; task k owns rows [off[k], off[k+1]) of X, Y, dY and dX.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mlora.h"
+
+namespace mlora {
+
+constexpr int kMaxK = MLORA_MAX_ADAPTERS;
+constexpr int kMaxRank = MLORA_MAX_RANK;
+
+typedef __bf16 bf16;
+
+// Split positions, ranks and scalings of one call, passed to kernels by value
+// (they land in the kernel-argument segment and are read with scalar loads).
+struct SegTable {
+  int K;
+  int off[kMaxK + 1];
+  int rank[kMaxK];
+  float s[kMaxK];
+};
+
+struct PtrTable {
+  const void* p[kMaxK];
+};
+
+struct OutTable {
+  float* p[kMaxK];
+};
+
+// Adapter that owns `row`, or -1 for rows outside every segment.
+__device__ __forceinline__ int find_segment(const SegTable& st, int row) {
+  int k = -1;
+  for (int i = 0; i < st.K; ++i) {
+    if (row >= st.off[i] && row < st.off[i + 1]) k = i;
+  }
+  return k;
+}
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return static_cast<float>(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+// fp32 -> bf16, round to nearest even, NaN/Inf propagate
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return static_cast<bf16>(v); }
+
+// Row stride (in elements) of the saved intermediate Z and of G: the largest rank
+// rounded up to a multiple of 16, so that rank-padded MFMA steps read zeros.
+inline int lowrank_ld(const mlora_problem* p) {
+  int rmax = 0;
+  for (int k = 0; k < p->K; ++k) rmax = p->ranks[k] > rmax ? p->ranks[k] : rmax;
+  return (rmax + 15) / 16 * 16;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Everything the launchers need, filled once per call from the validated problem.
+struct CallCtx {
+  int T, h, d, K, ldz;
+  int dtype;
+  SegTable st;
+  PtrTable A, B;
+  const void* W;
+  hipStream_t stream;
+};
+
+// ---- launchers (each returns a hipError_t; all work goes to ctx.stream) ----
+// generic_kernels.hip : any shape, fp32 or bf16 storage, plain VALU arithmetic
+hipError_t generic_fwd(const CallCtx& c, const void* X, void* Y, void* Z);
+hipError_t generic_bwd(const CallCtx& c, const void* X, const void* dY, const void* Z, void* dX,
+                       const OutTable& dA, const OutTable& dB, int accumulate, void* G);
+
+}  // namespace mlora

@@ -1,0 +1,126 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle
+on the same seeded inputs.  Tolerance: relative Frobenius error per output tensor
+(Y, dX, every dA_k, every dB_k) <= 2e-2 in bf16 mode and <= 1e-5 in fp32 mode."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2312_02515_amd import workloads as wl
+from tests.parity_util import TOL, check_full, check_sampled, np64, relerr, run_hip
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _inputs(T, h, d, tokens, ranks, dtype, lead=0, seed=0, scal=None):
+    off = [lead]
+    for t in tokens:
+        off.append(off[-1] + t)
+    assert off[-1] <= T
+    s = scal if scal is not None else [2.0] * len(ranks)
+    return wl.make_inputs(T, h, d, off, ranks, s, dtype, device=DEV, seed=seed, sigma_w=1.0 / np.sqrt(h))
+
+
+def test_tiny_f32_workload():
+    """Configuration 1 of the benchmark description, fp32 mode."""
+    w = wl.WORKLOADS["tiny_f32"]
+    inp = wl.make_workload_inputs(w, 0, device=DEV, seed=0)
+    out = run_hip(inp)
+    check_full(inp, out, TOL[torch.float32], label="tiny_f32")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("case", [
+    # T, h, d, tokens, ranks, lead
+    (0 + 300, 72, 136, [100, 0, 57, 130], [4, 8, 1, 24], 5),       # ragged, empty segment, uncovered rows
+    (513, 200, 264, [513], [16], 0),                                  # one adapter, ragged tail
+    (257, 64, 64, [], [], 0),                                         # no adapters: plain linear
+    (640, 256, 320, [64, 192, 128, 256], [8, 16, 32, 64], 0),         # tile-aligned mixed ranks
+    (700, 328, 264, [1, 63, 65, 300, 200], [64, 3, 128, 17, 40], 30),  # odd everything, rank up to 128
+])
+def test_small_shapes(dtype, case):
+    T, h, d, tokens, ranks, lead = case
+    inp = _inputs(T, h, d, tokens, ranks, dtype, lead=lead, seed=11, scal=[0.5 + 0.25 * i for i in range(len(ranks))])
+    out = run_hip(inp)
+    check_full(inp, out, TOL[dtype], label=f"{case}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_accumulate_and_skip_dx(dtype):
+    inp = _inputs(384, 128, 192, [128, 0, 200], [8, 4, 16], dtype, lead=16, seed=3)
+    base = run_hip(inp)
+    pre_a = [torch.full_like(t, 0.5) for t in base["dA"]]
+    pre_b = [torch.full_like(t, -1.5) for t in base["dB"]]
+    acc = run_hip(inp, accumulate=True, want_dx=False, preset_grads=(pre_a, pre_b))
+    assert acc["dX"] is None
+    for k in range(3):
+        ea = relerr(np64(acc["dA"][k]), np64(base["dA"][k]) + 0.5)
+        eb = relerr(np64(acc["dB"][k]), np64(base["dB"][k]) - 1.5)
+        assert ea <= 1e-6 and eb <= 1e-6
+    # empty segment: overwrite mode gave zeros, accumulate mode left the preset
+    assert not base["dA"][1].any() and not base["dB"][1].any()
+    assert torch.equal(acc["dA"][1], pre_a[1]) and torch.equal(acc["dB"][1], pre_b[1])
+    assert torch.equal(acc["Y"], base["Y"])
+
+
+def test_frozen_weight_and_inputs_untouched():
+    """W gets no gradient and is never written (section 3.3.1); neither are X, dY, A_k, B_k."""
+    inp = _inputs(256, 128, 128, [100, 156], [8, 16], torch.bfloat16, seed=5)
+    keep = [t.clone() for t in [inp.W, inp.X, inp.dY] + inp.A + inp.B]
+    run_hip(inp)
+    for a, b in zip(keep, [inp.W, inp.X, inp.dY] + inp.A + inp.B):
+        assert torch.equal(a, b)
+
+
+def test_deterministic():
+    inp = _inputs(1024, 256, 256, [300, 724], [16, 32], torch.bfloat16, seed=9)
+    a = run_hip(inp)
+    b = run_hip(inp)
+    assert torch.equal(a["Y"], b["Y"]) and torch.equal(a["dX"], b["dX"])
+    for k in range(2):
+        assert torch.equal(a["dA"][k], b["dA"][k]) and torch.equal(a["dB"][k], b["dB"][k])
+
+
+def test_isolation_on_gpu():
+    """Changing task 1's data and adapter leaves task 0's and 2's results bit-identical."""
+    inp = _inputs(768, 256, 256, [256, 256, 256], [8, 16, 8], torch.bfloat16, seed=21)
+    a = run_hip(inp)
+    inp.X[256:512] += 1.0
+    inp.dY[256:512] *= -2.0
+    inp.A[1].mul_(3.0)
+    inp.B[1].add_(0.25)
+    inp.scalings[1] = 7.0
+    b = run_hip(inp)
+    for lo, hi in ((0, 256), (512, 768)):
+        assert torch.equal(a["Y"][lo:hi], b["Y"][lo:hi]) and torch.equal(a["dX"][lo:hi], b["dX"][lo:hi])
+    for k in (0, 2):
+        assert torch.equal(a["dA"][k], b["dA"][k]) and torch.equal(a["dB"][k], b["dB"][k])
+    assert not torch.equal(a["Y"][256:512], b["Y"][256:512])
+
+
+def test_llama2_7b_qproj_full():
+    """Configuration 2, every output element against the oracle."""
+    w = wl.WORKLOADS["llama2_7b_qproj"]
+    inp = wl.make_workload_inputs(w, 0, device=DEV, seed=0)
+    out = run_hip(inp, poison=False)
+    errs = check_full(inp, out, TOL[torch.bfloat16], label=w.name)
+    print(w.name, {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+def _sampled_workload(name, proj, per_adapter=6, grad_adapters=None):
+    w = wl.WORKLOADS[name]
+    inp = wl.make_workload_inputs(w, proj, device=DEV, seed=0)
+    out = run_hip(inp, poison=False)
+    rows = wl.sample_rows(inp.seg_offsets, w.T, per_adapter, seed=proj)
+    errs = check_sampled(inp, out, TOL[torch.bfloat16], rows, grad_adapters=grad_adapters,
+                         label=f"{name}/{w.projections[proj].name}")
+    # properties that hold at any size: every output is finite, W untouched
+    assert torch.isfinite(out["Y"]).all() and torch.isfinite(out["dX"]).all()
+    print(name, w.projections[proj].name, "max err", f"{max(errs.values()):.2e}")
+
+
+@pytest.mark.parametrize("proj", [0, 2])
+def test_llama2_7b_mlp_sampled(proj):
+    """Configuration 3 at full size: sampled complete rows of Y and dX, all dA_k, dB_k."""
+    _sampled_workload("llama2_7b_mlp", proj)
