@@ -126,9 +126,12 @@ const char* mlora_status_string(mlora_status s);
 /* hipError_t (as int) of the last HIP failure seen by this thread's calls; 0 if none. */
 int mlora_last_hip_error(void);
 
-/* Selects which kernels the two entry points use, for testing and measurement:
- *   0 (default) fastest applicable path (MFMA kernels when shapes allow, else generic),
- *   1           generic kernels only.
+/* Selects which kernels the two entry points use, for testing and measurement (bit mask):
+ *   0 (default) fastest applicable path: MFMA kernels when the problem is bf16, h and d are
+ *               multiples of 64, every rank is a multiple of 8 and all buffers are 16-byte
+ *               aligned; the generic kernels otherwise,
+ *   bit 0       generic kernels for the two base products,
+ *   bit 1       generic kernels for the low-rank products (3 = generic everywhere).
  * Returns the previous value.  Process-wide. */
 int mlora_set_kernel_path(int path);
 

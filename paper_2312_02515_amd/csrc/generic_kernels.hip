@@ -133,54 +133,75 @@ __global__ void k_grad_A(const T* __restrict__ X, int h, const T* __restrict__ G
 }
 
 template <typename T>
-hipError_t fwd_t(const CallCtx& c, const T* X, T* Y, T* Z) {
-  if (c.K > 0) {
-    dim3 blk(32, 8);
-    hipLaunchKernelGGL(k_lowrank_rows<T>, dim3((c.T + 7) / 8), blk, 0, c.stream, X, c.T, c.h, Z, c.ldz, c.st, c.A, 0);
-  }
-  dim3 grid((c.T + 63) / 64, (c.d + 63) / 64);
-  hipLaunchKernelGGL((k_gemm_lora<T, false>), grid, dim3(256), 0, c.stream, X, static_cast<const T*>(c.W), Y, c.T,
-                     c.d, c.h, Z, c.ldz, c.st, c.B);
+hipError_t lowrank_t(const CallCtx& c, const T* In, int inner, T* Out, const PtrTable& M, int mode) {
+  if (c.K > 0 && c.T > 0)
+    hipLaunchKernelGGL(k_lowrank_rows<T>, dim3((c.T + 7) / 8), dim3(32, 8), 0, c.stream, In, c.T, inner, Out, c.ldz,
+                       c.st, M, mode);
   return hipGetLastError();
 }
 
-template <typename T>
-hipError_t bwd_t(const CallCtx& c, const T* X, const T* dY, const T* Z, T* dX, const OutTable& dA,
-                 const OutTable& dB, int accumulate, T* G) {
-  int rmax = 0;
-  for (int k = 0; k < c.K; ++k) rmax = c.st.rank[k] > rmax ? c.st.rank[k] : rmax;
-  if (c.K > 0 && c.T > 0) {
-    hipLaunchKernelGGL(k_lowrank_rows<T>, dim3((c.T + 7) / 8), dim3(32, 8), 0, c.stream, dY, c.T, c.d, G, c.ldz,
-                       c.st, c.B, 1);
-  }
-  if (c.K > 0) {
-    hipLaunchKernelGGL(k_grad_B<T>, dim3((c.d + 255) / 256, rmax, c.K), dim3(256), 0, c.stream, Z, c.ldz, dY, c.d,
-                       c.st, dB, accumulate);
-    hipLaunchKernelGGL(k_grad_A<T>, dim3((c.h + 255) / 256, rmax, c.K), dim3(256), 0, c.stream, X, c.h,
-                       static_cast<const T*>(G), c.ldz, c.st, dA, accumulate);
-  }
-  if (dX != nullptr && c.T > 0) {
-    dim3 grid((c.T + 63) / 64, (c.h + 63) / 64);
-    hipLaunchKernelGGL((k_gemm_lora<T, true>), grid, dim3(256), 0, c.stream, dY, static_cast<const T*>(c.W), dX,
-                       c.T, c.h, c.d, static_cast<const T*>(G), c.ldz, c.st, c.A);
+template <typename T, bool TRANSB>
+hipError_t gemm_t(const CallCtx& c, const T* A, T* C, int N, int Kd, const T* L, const PtrTable& R) {
+  if (c.T > 0) {
+    dim3 grid((c.T + 63) / 64, (N + 63) / 64);
+    hipLaunchKernelGGL((k_gemm_lora<T, TRANSB>), grid, dim3(256), 0, c.stream, A, static_cast<const T*>(c.W), C, c.T,
+                       N, Kd, L, c.ldz, c.st, R);
   }
   return hipGetLastError();
+}
+
+int max_rank(const CallCtx& c) {
+  int rmax = 0;
+  for (int k = 0; k < c.K; ++k) rmax = c.st.rank[k] > rmax ? c.st.rank[k] : rmax;
+  return rmax;
 }
 
 }  // namespace
 
-hipError_t generic_fwd(const CallCtx& c, const void* X, void* Y, void* Z) {
-  if (c.dtype == MLORA_F32) return fwd_t<float>(c, static_cast<const float*>(X), static_cast<float*>(Y), static_cast<float*>(Z));
-  return fwd_t<bf16>(c, static_cast<const bf16*>(X), static_cast<bf16*>(Y), static_cast<bf16*>(Z));
+#define DISPATCH(expr_f32, expr_bf16) ((c.dtype == MLORA_F32) ? (expr_f32) : (expr_bf16))
+
+hipError_t generic_Z(const CallCtx& c, const void* X, void* Z) {
+  return DISPATCH(lowrank_t<float>(c, (const float*)X, c.h, (float*)Z, c.A, 0),
+                  lowrank_t<bf16>(c, (const bf16*)X, c.h, (bf16*)Z, c.A, 0));
 }
 
-hipError_t generic_bwd(const CallCtx& c, const void* X, const void* dY, const void* Z, void* dX,
-                       const OutTable& dA, const OutTable& dB, int accumulate, void* G) {
+hipError_t generic_G(const CallCtx& c, const void* dY, void* G) {
+  return DISPATCH(lowrank_t<float>(c, (const float*)dY, c.d, (float*)G, c.B, 1),
+                  lowrank_t<bf16>(c, (const bf16*)dY, c.d, (bf16*)G, c.B, 1));
+}
+
+hipError_t generic_gemm_fwd(const CallCtx& c, const void* X, void* Y, const void* Z) {
+  return DISPATCH((gemm_t<float, false>(c, (const float*)X, (float*)Y, c.d, c.h, (const float*)Z, c.B)),
+                  (gemm_t<bf16, false>(c, (const bf16*)X, (bf16*)Y, c.d, c.h, (const bf16*)Z, c.B)));
+}
+
+hipError_t generic_gemm_bwd(const CallCtx& c, const void* dY, void* dX, const void* G) {
+  return DISPATCH((gemm_t<float, true>(c, (const float*)dY, (float*)dX, c.h, c.d, (const float*)G, c.A)),
+                  (gemm_t<bf16, true>(c, (const bf16*)dY, (bf16*)dX, c.h, c.d, (const bf16*)G, c.A)));
+}
+
+hipError_t generic_dB(const CallCtx& c, const void* Z, const void* dY, const OutTable& dB, int accumulate) {
+  if (c.K == 0) return hipSuccess;
+  dim3 grid((c.d + 255) / 256, max_rank(c), c.K);
   if (c.dtype == MLORA_F32)
-    return bwd_t<float>(c, static_cast<const float*>(X), static_cast<const float*>(dY), static_cast<const float*>(Z),
-                        static_cast<float*>(dX), dA, dB, accumulate, static_cast<float*>(G));
-  return bwd_t<bf16>(c, static_cast<const bf16*>(X), static_cast<const bf16*>(dY), static_cast<const bf16*>(Z),
-                     static_cast<bf16*>(dX), dA, dB, accumulate, static_cast<bf16*>(G));
+    hipLaunchKernelGGL(k_grad_B<float>, grid, dim3(256), 0, c.stream, (const float*)Z, c.ldz, (const float*)dY, c.d,
+                       c.st, dB, accumulate);
+  else
+    hipLaunchKernelGGL(k_grad_B<bf16>, grid, dim3(256), 0, c.stream, (const bf16*)Z, c.ldz, (const bf16*)dY, c.d,
+                       c.st, dB, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t generic_dA(const CallCtx& c, const void* X, const void* G, const OutTable& dA, int accumulate) {
+  if (c.K == 0) return hipSuccess;
+  dim3 grid((c.h + 255) / 256, max_rank(c), c.K);
+  if (c.dtype == MLORA_F32)
+    hipLaunchKernelGGL(k_grad_A<float>, grid, dim3(256), 0, c.stream, (const float*)X, c.h, (const float*)G, c.ldz,
+                       c.st, dA, accumulate);
+  else
+    hipLaunchKernelGGL(k_grad_A<bf16>, grid, dim3(256), 0, c.stream, (const bf16*)X, c.h, (const bf16*)G, c.ldz,
+                       c.st, dA, accumulate);
+  return hipGetLastError();
 }
 
 }  // namespace mlora

@@ -67,6 +67,23 @@ void fill_ctx(const mlora_problem* p, void* stream, CallCtx* c) {
   }
 }
 
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// The MFMA GEMMs take bf16 problems whose feature sizes are multiples of 64, whose ranks are
+// multiples of 8 and whose buffers are 16-byte aligned; everything else runs the generic kernels.
+bool mfma_shapes_ok(const mlora_problem* p) {
+  if (p->dtype != MLORA_BF16 || p->T < 1) return false;
+  if (!gemm_mfma_ok((int)p->T, (int)p->d, (int)p->h) || !gemm_mfma_ok((int)p->T, (int)p->h, (int)p->d)) return false;
+  if (!aligned16(p->W)) return false;
+  for (int k = 0; k < p->K; ++k) {
+    if (p->ranks[k] % 8 != 0 || !aligned16(p->A[k]) || !aligned16(p->B[k])) return false;
+  }
+  return true;
+}
+
+bool mfma_gemm_applies(const mlora_problem* p) { return !(g_kernel_path.load() & 1) && mfma_shapes_ok(p); }
+bool mfma_lowrank_applies(const mlora_problem* p) { return !(g_kernel_path.load() & 2) && mfma_shapes_ok(p); }
+
 mlora_status hip_status(hipError_t e) {
   if (e == hipSuccess) return MLORA_OK;
   g_last_hip_error = (int)e;
@@ -103,7 +120,18 @@ mlora_status mlora_lora_fwd(const mlora_problem* p, const void* X, void* Y, void
   if (workspace == nullptr || workspace_bytes < mlora_lora_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
   CallCtx c;
   fill_ctx(p, hip_stream, &c);
-  return hip_status(generic_fwd(c, X, Y, saved));
+  hipError_t e;
+  if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(saved))
+    e = lowrank_rows_mfma(c, (const bf16*)X, c.h, (bf16*)saved, c.A, true);
+  else
+    e = generic_Z(c, X, saved);
+  if (e != hipSuccess) return hip_status(e);
+  if (mfma_gemm_applies(p) && aligned16(X) && aligned16(Y) && aligned16(saved))
+    e = gemm_mfma((const bf16*)X, (const bf16*)p->W, (bf16*)Y, c.T, c.d, c.h, true, (const bf16*)saved, c.ldz, c.st,
+                  c.B, c.stream);
+  else
+    e = generic_gemm_fwd(c, X, Y, saved);
+  return hip_status(e);
 }
 
 mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* dY, const void* saved, void* dX,
@@ -126,7 +154,25 @@ mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* d
     tb.p[k] = k < p->K ? dB[k] : nullptr;
   }
   if (p->T == 0 && accumulate) return MLORA_OK;
-  return hip_status(generic_bwd(c, X, dY, saved, dX, ta, tb, accumulate ? 1 : 0, workspace));
+  void* G = workspace;
+  hipError_t e;
+  if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(dY) && aligned16(saved) && aligned16(G)) {
+    e = lowrank_rows_mfma(c, (const bf16*)dY, c.d, (bf16*)G, c.B, false);
+    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)dY, c.d, (const bf16*)saved, tb, accumulate ? 1 : 0, false);
+    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)X, c.h, (const bf16*)G, ta, accumulate ? 1 : 0, true);
+  } else {
+    e = generic_G(c, dY, G);
+    if (e == hipSuccess) e = generic_dB(c, saved, dY, tb, accumulate ? 1 : 0);
+    if (e == hipSuccess) e = generic_dA(c, X, G, ta, accumulate ? 1 : 0);
+  }
+  if (e == hipSuccess && dX != nullptr && p->T > 0) {
+    if (mfma_gemm_applies(p) && aligned16(dY) && aligned16(dX) && aligned16(G))
+      e = gemm_mfma((const bf16*)dY, (const bf16*)p->W, (bf16*)dX, c.T, c.h, c.d, false, (const bf16*)G, c.ldz, c.st,
+                    c.A, c.stream);
+    else
+      e = generic_gemm_bwd(c, dY, dX, G);
+  }
+  return hip_status(e);
 }
 
 const char* mlora_status_string(mlora_status s) {

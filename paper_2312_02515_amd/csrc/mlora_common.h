@@ -69,10 +69,24 @@ struct CallCtx {
   hipStream_t stream;
 };
 
-// ---- launchers (each returns a hipError_t; all work goes to ctx.stream) ----
+// ---- launchers (each returns a hipError_t; all work goes to c.stream) ----
 // generic_kernels.hip : any shape, fp32 or bf16 storage, plain VALU arithmetic
-hipError_t generic_fwd(const CallCtx& c, const void* X, void* Y, void* Z);
-hipError_t generic_bwd(const CallCtx& c, const void* X, const void* dY, const void* Z, void* dX,
-                       const OutTable& dA, const OutTable& dB, int accumulate, void* G);
+hipError_t generic_Z(const CallCtx& c, const void* X, void* Z);                        // Z = s x A
+hipError_t generic_G(const CallCtx& c, const void* dY, void* G);                       // G = s dy B^T
+hipError_t generic_gemm_fwd(const CallCtx& c, const void* X, void* Y, const void* Z);  // Y = X W + Z B
+hipError_t generic_gemm_bwd(const CallCtx& c, const void* dY, void* dX, const void* G);  // dX = dY W^T + G A^T
+hipError_t generic_dB(const CallCtx& c, const void* Z, const void* dY, const OutTable& dB, int accumulate);
+hipError_t generic_dA(const CallCtx& c, const void* X, const void* G, const OutTable& dA, int accumulate);
+
+// gemm_mfma.hip : bf16 MFMA GEMM with the LoRA term as extra contraction steps
+bool gemm_mfma_ok(int M, int N, int Kd);
+hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int Kd, bool nn, const bf16* L, int ldz,
+                     const SegTable& st, const PtrTable& R, hipStream_t stream);
+
+
+// lowrank_mfma.hip : bf16 MFMA kernels for Z, G (row-local) and dA_k, dB_k (reduce over a task's tokens)
+hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* Out, const PtrTable& M, bool a_major);
+hipError_t grad_mfma(const CallCtx& c, const bf16* Big, int wide, const bf16* Small, const OutTable& out,
+                     int accumulate, bool wide_first);
 
 }  // namespace mlora

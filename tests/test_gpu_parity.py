@@ -38,6 +38,10 @@ def test_tiny_f32_workload():
     (257, 64, 64, [], [], 0),                                         # no adapters: plain linear
     (640, 256, 320, [64, 192, 128, 256], [8, 16, 32, 64], 0),         # tile-aligned mixed ranks
     (700, 328, 264, [1, 63, 65, 300, 200], [64, 3, 128, 17, 40], 30),  # odd everything, rank up to 128
+    # shapes the MFMA kernels take (h, d multiples of 64, ranks multiples of 8), ragged in every other way
+    (1000, 192, 320, [100, 0, 333, 500], [8, 24, 128, 64], 7),        # rank 128, empty segment, tails
+    (900, 128, 64, [130, 700], [16, 8], 3),                           # narrow output, small ranks
+    (1537, 448, 576, [1, 255, 257, 1024], [64, 32, 8, 16], 0),        # one-token task, tile-straddling tasks
 ])
 def test_small_shapes(dtype, case):
     T, h, d, tokens, ranks, lead = case
@@ -62,6 +66,19 @@ def test_accumulate_and_skip_dx(dtype):
     assert not base["dA"][1].any() and not base["dB"][1].any()
     assert torch.equal(acc["dA"][1], pre_a[1]) and torch.equal(acc["dB"][1], pre_b[1])
     assert torch.equal(acc["Y"], base["Y"])
+
+
+@pytest.mark.parametrize("path", [1, 2, 3])
+def test_generic_and_mfma_kernels_agree(path):
+    """Every mix of generic and MFMA kernels meets the same tolerance on an MFMA-eligible shape."""
+    from paper_2312_02515_amd import binding as mb
+    inp = _inputs(777, 256, 384, [300, 77, 400], [16, 64, 8], torch.bfloat16, seed=13)
+    old = mb.set_kernel_path(path)
+    try:
+        out = run_hip(inp)
+    finally:
+        mb.set_kernel_path(old)
+    check_full(inp, out, TOL[torch.bfloat16], label=f"path{path}")
 
 
 def test_frozen_weight_and_inputs_untouched():
