@@ -135,6 +135,17 @@ int mlora_last_hip_error(void);
  * Returns the previous value.  Process-wide. */
 int mlora_set_kernel_path(int path);
 
+/* Measurement aid for the dominant kernel (the MFMA base product with its LoRA steps).
+ * While enabled, every launch of that kernel by this process is bracketed by a pair of HIP
+ * events recorded on the launch stream (at most 4096 launches are kept; the events are
+ * created on first use and live until the process ends).  Returns the previous setting. */
+int mlora_profile_gemm(int enable);
+
+/* Waits for the recorded launches to finish, returns the sum of their durations in
+ * milliseconds, the sum of their algorithmic flops (2 M N K plus 2 t_k r_k N per task) and
+ * their count through the non-NULL pointers (HOST), and forgets them. */
+mlora_status mlora_profile_gemm_read(double* ms_total, double* flops_total, int* launches);
+
 #ifdef __cplusplus
 }
 #endif

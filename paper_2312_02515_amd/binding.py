@@ -24,7 +24,8 @@ STATUS_NAMES = {0: "MLORA_OK", 1: "MLORA_ERR_NULL", 2: "MLORA_ERR_SHAPE", 3: "ML
                 4: "MLORA_ERR_RANK", 5: "MLORA_ERR_DTYPE", 6: "MLORA_ERR_WORKSPACE", 7: "MLORA_ERR_HIP"}
 
 EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_validate", "mlora_lora_fwd",
-           "mlora_lora_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path"]
+           "mlora_lora_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_gemm",
+           "mlora_profile_gemm_read"]
 
 
 class MloraError(RuntimeError):
@@ -71,6 +72,11 @@ def _load() -> ctypes.CDLL:
     l.mlora_last_hip_error.argtypes = []
     l.mlora_set_kernel_path.restype = ctypes.c_int
     l.mlora_set_kernel_path.argtypes = [ctypes.c_int]
+    l.mlora_profile_gemm.restype = ctypes.c_int
+    l.mlora_profile_gemm.argtypes = [ctypes.c_int]
+    l.mlora_profile_gemm_read.restype = ctypes.c_int
+    l.mlora_profile_gemm_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(ctypes.c_int)]
     return l
 
 
@@ -164,3 +170,16 @@ def mlora_lora_bwd(prob: Problem, X: torch.Tensor, dY: torch.Tensor, saved: torc
 
 def set_kernel_path(path: int) -> int:
     return int(lib.mlora_set_kernel_path(int(path)))
+
+
+def profile_gemm(enable: bool) -> bool:
+    return bool(lib.mlora_profile_gemm(1 if enable else 0))
+
+
+def profile_gemm_read():
+    """(total ms, total algorithmic flops, launches) of the MFMA base-product kernel since the last read."""
+    ms, fl, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int(0)
+    st = lib.mlora_profile_gemm_read(ctypes.byref(ms), ctypes.byref(fl), ctypes.byref(n))
+    if st != 0:
+        raise MloraError(st, "mlora_profile_gemm_read")
+    return ms.value, fl.value, n.value

@@ -23,6 +23,9 @@
 //     each lane four consecutive contraction indices of one output column.
 // The MFMA is issued with the weight fragment as its first operand so that each
 // lane ends up with four consecutive output columns of one row (8-byte stores).
+#include <mutex>
+#include <vector>
+
 #include "mlora_common.h"
 
 namespace mlora {
@@ -241,7 +244,45 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
   }
 }
 
+// ---- optional per-launch timing of this kernel with HIP events on the launch stream ----
+struct GemmProfile {
+  bool on = false;
+  std::vector<hipEvent_t> start, stop;
+  std::vector<double> flops;
+  size_t used = 0;
+};
+GemmProfile g_prof;
+std::mutex g_prof_mu;
+constexpr size_t kMaxProfiled = 4096;
+
 }  // namespace
+
+int gemm_profile_enable(int enable) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  const int old = g_prof.on ? 1 : 0;
+  g_prof.on = enable != 0;
+  return old;
+}
+
+// Waits for every recorded launch, sums durations and flops, then forgets them.
+hipError_t gemm_profile_read(double* ms_total, double* flops_total, int* launches) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  double ms = 0, fl = 0;
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    hipError_t e = hipEventSynchronize(g_prof.stop[i]);
+    if (e != hipSuccess) return e;
+    float t = 0.f;
+    e = hipEventElapsedTime(&t, g_prof.start[i], g_prof.stop[i]);
+    if (e != hipSuccess) return e;
+    ms += t;
+    fl += g_prof.flops[i];
+  }
+  if (ms_total) *ms_total = ms;
+  if (flops_total) *flops_total = fl;
+  if (launches) *launches = (int)g_prof.used;
+  g_prof.used = 0;
+  return hipSuccess;
+}
 
 bool gemm_mfma_ok(int M, int N, int Kd) { return M >= 1 && (N % 64) == 0 && (Kd % 64) == 0 && N >= 64 && Kd >= 64; }
 
@@ -250,13 +291,36 @@ hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int K
                      const SegTable& st, const PtrTable& R, hipStream_t stream) {
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const dim3 grid(tiles_m * tiles_n);
+  int slot = -1;
+  {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof.on && g_prof.used < kMaxProfiled) {
+      if (g_prof.used == g_prof.start.size()) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
+          g_prof.start.push_back(a);
+          g_prof.stop.push_back(b);
+          g_prof.flops.push_back(0.0);
+        }
+      }
+      if (g_prof.used < g_prof.start.size()) {
+        slot = (int)g_prof.used++;
+        double f = 2.0 * M * (double)N * Kd;
+        for (int k = 0; k < st.K; ++k) f += 2.0 * (st.off[k + 1] - st.off[k]) * (double)st.rank[k] * N;
+        g_prof.flops[slot] = f;
+        (void)hipEventRecord(g_prof.start[slot], stream);
+      }
+    }
+  }
   if (nn)
     hipLaunchKernelGGL((k_gemm_mfma<2, 4, true>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
                        tiles_m, tiles_n);
   else
     hipLaunchKernelGGL((k_gemm_mfma<2, 4, false>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
                        tiles_m, tiles_n);
-  return hipGetLastError();
+  const hipError_t err = hipGetLastError();
+  if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], stream);
+  return err;
 }
 
 }  // namespace mlora

@@ -193,4 +193,10 @@ int mlora_last_hip_error(void) { return g_last_hip_error; }
 
 int mlora_set_kernel_path(int path) { return g_kernel_path.exchange(path); }
 
+int mlora_profile_gemm(int enable) { return gemm_profile_enable(enable); }
+
+mlora_status mlora_profile_gemm_read(double* ms_total, double* flops_total, int* launches) {
+  return hip_status(gemm_profile_read(ms_total, flops_total, launches));
+}
+
 }  // extern "C"

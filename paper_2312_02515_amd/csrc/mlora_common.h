@@ -83,6 +83,8 @@ bool gemm_mfma_ok(int M, int N, int Kd);
 hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int Kd, bool nn, const bf16* L, int ldz,
                      const SegTable& st, const PtrTable& R, hipStream_t stream);
 
+int gemm_profile_enable(int enable);
+hipError_t gemm_profile_read(double* ms_total, double* flops_total, int* launches);
 
 // lowrank_mfma.hip : bf16 MFMA kernels for Z, G (row-local) and dA_k, dB_k (reduce over a task's tokens)
 hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* Out, const PtrTable& M, bool a_major);

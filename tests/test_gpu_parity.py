@@ -141,3 +141,18 @@ def _sampled_workload(name, proj, per_adapter=6, grad_adapters=None):
 def test_llama2_7b_mlp_sampled(proj):
     """Configuration 3 at full size: sampled complete rows of Y and dX, all dA_k, dB_k."""
     _sampled_workload("llama2_7b_mlp", proj)
+
+
+@pytest.mark.parametrize("proj", [0, 4, 6])
+def test_llama2_13b_layer_sampled(proj):
+    """Configuration 4 at full size (q_proj, gate_proj, down_proj shapes), in the launch
+    configuration the benchmark times: sampled complete rows of Y and dX, all dA_k, dB_k."""
+    _sampled_workload("llama2_13b_layer", proj, per_adapter=4)
+
+
+@pytest.mark.parametrize("proj", [0, 1])
+def test_llama2_70b_mlp_stage_sampled(proj):
+    """Configuration 5 at full size: sampled rows, and whole dA_k, dB_k for a seeded third of
+    the 32 adapters (each is an independent exact reduction)."""
+    picks = [0, 2, 3, 7, 11, 13, 16, 20, 25, 28, 31]
+    _sampled_workload("llama2_70b_mlp_stage", proj, per_adapter=2, grad_adapters=picks)
