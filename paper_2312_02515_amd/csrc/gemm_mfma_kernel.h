@@ -1,0 +1,319 @@
+// bf16 MFMA GEMM kernel with the LoRA term folded in as extra contraction steps (gfx950).
+//
+//   C[M,N] = A[M,Kd] * op(Bm) + rows_k( L[rows_k, :r_k] * R_k )
+//     NN = true  (forward,  Eq. "forward"):      Bm = W [Kd,N] (contraction index = rows of W),  R_k = B_k [r_k, N]
+//     NN = false (backward, Eq. "grad_output"):  Bm = W [N,Kd] (contraction index = columns),     R_k = A_k [N, r_k]
+//
+// Tile 256 x 256 x 32, 8 waves (2 x 4, wave tile 128 x 64), fp32 accumulation in
+// v_mfma_f32_32x32x16_bf16 with the accumulators in AccVGPRs, 4-stage ring of LDS tiles filled by
+// direct global->LDS loads (global_load_lds_dwordx4, 16 B per lane).  A wave-wide direct load
+// fills 1 KiB of contiguous LDS, so the bank-conflict swizzle is applied by choosing which global
+// 16-byte chunk each lane fetches:
+//   * K-contiguous tiles (A, and Bm when !NN): 256 rows x 64 B; chunk c of row r sits at chunk
+//     position c ^ ((r >> 2) & 3); read with ds_read_b128.
+//   * Bm when NN: 32 contraction rows x 512 B; chunk c of row k sits at c ^ ((k & 3) << 2); read
+//     with ds_read_b64_tr_b16, which hands each lane four consecutive contraction indices of one
+//     output column -- no transposed copy of W is ever made.
+// The MFMA takes the weight fragment as its first operand so that each lane ends up with four
+// consecutive output columns of one row; the output tile goes through LDS once more so that it
+// leaves the CU as full 128-byte row segments.
+#pragma once
+
+#include "mfma_staging.h"
+#include "mlora_common.h"
+
+namespace mlora {
+namespace gemmk {
+
+using namespace stage;
+
+constexpr int BM = 256, BN = 256;
+
+// ------------------------------------------------------------------------------------------
+// Schedule: contraction tiles of 32, NS-stage ring (NS = 4 or 5), and every memory
+// instruction placed between two MFMAs.  Issuing a vector-memory load keeps
+// the SIMD's issue port busy for some cycles; when a wave issues its loads back to back the
+// matrix pipe idles meanwhile, when each load follows an MFMA it hides behind that MFMA's
+// 32 cycles.  The same holds for the LDS fragment reads, which are issued one MFMA step ahead
+// of their use (two register sets of fragments).
+//   iteration kt (two MFMA steps):
+//     step 0: MFMAs on the fragments of (tile kt, step 0); between them: LDS reads of (kt, step 1)
+//             and the direct-to-LDS loads of tile kt+NS-1
+//     step 1: MFMAs on (kt, step 1); between them: LDS reads of (kt+1, step 0)
+//     s_waitcnt so that this wave's loads of tile kt+2 have landed; barrier
+//   so at the barrier that ends iteration kt every wave has finished reading tile kt (its stage
+//   is refilled during iteration kt+1) and tile kt+2 is visible to all (read from kt+1 on).
+// ------------------------------------------------------------------------------------------
+template <int WAVES_M, int WAVES_N, bool NN, int NS>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
+    const bf16* __restrict__ A, const bf16* __restrict__ Bm, bf16* __restrict__ C, int M, int N, int Kd,
+    const bf16* __restrict__ L, int ldz, SegTable st, PtrTable R, int tiles_m, int tiles_n) {
+  constexpr int BK = 32;
+  constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int FM = WM / 32, FN = WN / 32;
+  constexpr int NMF = FM * FN;                 // MFMAs per step
+  constexpr int NOPS = FM + FN;                // fragment reads per step
+  constexpr int RSLOTS = (NOPS + 1) / 2;       // two fragment reads behind each of the first MFMAs
+  constexpr int ROWB = BK * 2, CPR = BK / 8, RW = 256 / ROWB, RPI = 1024 / ROWB;
+  constexpr int TILE_BYTES = BM * ROWB;        // 16 KiB; the NN weight tile (32 x 512 B) has the same size
+  constexpr int LPW = TILE_BYTES / 1024 / NW;  // wave-wide loads per wave per operand tile
+  constexpr int PER_TILE = 2 * LPW;
+  static_assert(NS == 4 || NS == 5, "ring depth");
+  static_assert(RSLOTS + PER_TILE <= NMF, "not enough MFMAs per step to hide the memory instructions");
+
+  __shared__ __attribute__((aligned(1024))) char sA0[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sA1[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sA2[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sA3[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sA4[NS > 4 ? TILE_BYTES : 16];
+  __shared__ __attribute__((aligned(1024))) char sB0[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sB1[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sB2[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sB3[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sB4[NS > 4 ? TILE_BYTES : 16];
+  char* const sA[5] = {sA0, sA1, sA2, sA3, sA4};
+  char* const sB[5] = {sB0, sB1, sB2, sB3, sB4};
+
+  const int total = tiles_m * tiles_n;
+  const int bid = blockIdx.x;
+  const int per = total / 8, rem = total % 8;
+  const int xcd = bid % 8, local = bid / 8;
+  const int t = xcd * per + (xcd < rem ? xcd : rem) + local;
+  constexpr int GM = 8;
+  const int gsize = GM * tiles_n;
+  const int group = t / gsize;
+  const int first_m = group * GM;
+  const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int in_g = t - group * gsize;
+  const int tm = first_m + in_g % gm, tn = in_g / gm;
+  const int row0 = tm * BM, col0 = tn * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  // Accumulators in AccVGPRs: naming one "a" register operand makes the compiler select the
+  // AGPR form of the MFMAs, which keeps the accumulator traffic off the VGPR ports that the
+  // LDS fragment reads write through.
+  {
+    float agpr_hint = 0.f;
+    asm volatile("" : "+a"(agpr_hint));
+  }
+
+  // ---- direct-to-LDS loads: wave-uniform base of the tile's rows (advanced per contraction
+  // tile with scalar arithmetic) plus a constant 32-bit per-lane byte offset
+  const char* abase = reinterpret_cast<const char*>(A + (size_t)row0 * Kd);
+  const char* bbase = NN ? reinterpret_cast<const char*>(Bm + col0) : reinterpret_cast<const char*>(Bm + (size_t)col0 * Kd);
+  unsigned aoff[LPW], boff[LPW];
+#pragma unroll
+  for (int it = 0; it < LPW; ++it) {
+    const int w = wave + NW * it;
+    {
+      const int rl = RPI * w + lane / CPR;
+      const int c = (lane % CPR) ^ ((rl / RW) % CPR);
+      int gr = row0 + rl;
+      gr = gr < M ? gr : M - 1;
+      aoff[it] = (unsigned)(((size_t)(gr - row0) * Kd + c * 8) * 2);
+    }
+    if (NN) {
+      const int kr = 2 * w + (lane >> 5);
+      const int c = (lane & 31) ^ ((kr & 3) << 2);
+      int n = col0 + c * 8;
+      n = n < N ? n : N - 8;
+      boff[it] = (unsigned)(((size_t)kr * N + (n - col0)) * 2);
+    } else {
+      const int rl = RPI * w + lane / CPR;
+      const int c = (lane % CPR) ^ ((rl / RW) % CPR);
+      int gn = col0 + rl;
+      gn = gn < N ? gn : N - 1;
+      boff[it] = (unsigned)(((size_t)(gn - col0) * Kd + c * 8) * 2);
+    }
+  }
+  const size_t bstep = (NN ? (size_t)BK * N : (size_t)BK) * 2;  // bytes per contraction tile
+
+  // the idx-th of the PER_TILE wave-wide loads of contraction tile kt
+  auto issue_one = [&](int kt, int idx, char* sa, char* sb) {
+    if (idx < LPW)
+      load_lds_16B_sbase(abase + (size_t)kt * (BK * 2), aoff[idx], sa + (wave + NW * idx) * 1024);
+    else
+      load_lds_16B_sbase(bbase + (size_t)kt * bstep, boff[idx - LPW], sb + (wave + NW * (idx - LPW)) * 1024);
+  };
+
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int fsw = (l32 / RW) % CPR;
+  const int a_row_off = (wm * WM + l32) * ROWB;
+  const int b_row_off = (wn * WN + l32) * ROWB;
+  const int L16 = lane & 15, blk = lane >> 4, kq = L16 >> 2;
+  const int nn_k = 8 * (blk >> 1) + kq;
+  const int nn_n = wn * WN + 16 * (blk & 1) + 4 * (L16 & 3);
+
+  // fragment read number op (0..NOPS-1) of step ks of the tile in (sa, sb): weight fragments first
+  auto read_op = [&](const char* sa, const char* sb, int ks, int op, bf16x8 (&af)[FM], bf16x8 (&bfr)[FN]) {
+    const int coff = ((2 * ks + lhi) ^ fsw) << 4;
+    if (op < FN) {
+      const int j = op;
+      if (NN) {
+        const int k = 16 * ks + nn_k;
+        const int n = nn_n + 32 * j;
+        const int phys = (n >> 3) ^ (kq << 2);
+        const char* p0 = sb + k * 512 + phys * 16 + (n & 7) * 2;
+        bfr[j] = lds_read_tr_pair(p0, p0 + 4 * 512);
+      } else {
+        bfr[j] = *(const bf16x8*)(sb + b_row_off + j * 32 * ROWB + coff);
+      }
+    } else {
+      const int i = op - FN;
+      af[i] = *(const bf16x8*)(sa + a_row_off + i * 32 * ROWB + coff);
+    }
+  };
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  bf16x8 af[2][FM], bfr[2][FN];
+
+  // one MFMA step on fragment set `cur`; behind MFMA number m: fragment reads 2m, 2m+1 of the
+  // next step into set `cur ^ 1` (if rd), and, in the last PER_TILE slots, one load of tile ld_kt (if ld)
+  auto step = [&](int cur, bool rd, const char* rsa, const char* rsb, int rks, bool ld, int ld_kt, char* lsa,
+                  char* lsb) {
+#pragma unroll
+    for (int m = 0; m < NMF; ++m) {
+      const int i = m / FN, j = m % FN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+      if (rd && m < RSLOTS) {
+        read_op(rsa, rsb, rks, 2 * m, af[cur ^ 1], bfr[cur ^ 1]);
+        if (2 * m + 1 < NOPS) read_op(rsa, rsb, rks, 2 * m + 1, af[cur ^ 1], bfr[cur ^ 1]);
+      }
+      if (ld && m >= NMF - PER_TILE) issue_one(ld_kt, m - (NMF - PER_TILE), lsa, lsb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  const int KT = Kd / BK;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < KT) {
+#pragma unroll
+      for (int idx = 0; idx < PER_TILE; ++idx) issue_one(s, idx, sA[s], sB[s]);
+    }
+  // tiles 0 and 1 landed (younger tiles may still be in flight)
+  if (KT >= NS - 1)
+    wait_vmcnt<(NS - 3) * PER_TILE>();
+  else
+    wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
+
+  for (int kt0 = 0; kt0 < KT; kt0 += NS) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int kt = kt0 + s;
+      if (kt < KT) {
+        const bool ld = kt + NS - 1 < KT;
+        step(0, true, sA[s], sB[s], 1, ld, kt + NS - 1, sA[(s + NS - 1) % NS], sB[(s + NS - 1) % NS]);
+        step(1, kt + 1 < KT, sA[(s + 1) % NS], sB[(s + 1) % NS], 0, false, 0, nullptr, nullptr);
+        if (ld)  // every tile up to kt+NS-1 has been issued: tiles kt+3.. may stay in flight
+          wait_vmcnt<(NS - 3) * PER_TILE>();
+        else
+          wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+      }
+    }
+  }
+
+  // ---- LoRA extension steps (the stages are free now: every load has landed and every wave
+  // passed the last barrier after its last fragment read)
+  auto ext_compute = [&](int ksteps) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      if (ks < ksteps) {
+#pragma unroll
+        for (int op = 0; op < NOPS; ++op) read_op(sA0, sB0, ks, op, af[0], bfr[0]);
+#pragma unroll
+        for (int m = 0; m < NMF; ++m) {
+          const int i = m / FN, j = m % FN;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[0][j], af[0][i], acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  };
+  const int rend = (row0 + BM) < M ? (row0 + BM) : M;
+  for (int k = 0; k < st.K; ++k) {
+    const int lo = st.off[k] > row0 ? st.off[k] : row0;
+    const int hi = st.off[k + 1] < rend ? st.off[k + 1] : rend;
+    if (lo >= hi) continue;
+    const int r = st.rank[k];
+    const bf16* Rk = static_cast<const bf16*>(R.p[k]);
+    for (int q0 = 0; q0 < r; q0 += BK) {
+      __syncthreads();
+      for (int e = tid; e < BM * CPR; e += NT) {
+        const int rl = e / CPR, c = e % CPR;
+        const int row = row0 + rl, q = q0 + c * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row >= lo && row < hi && q < ldz) v = *(const uint4*)(L + (size_t)row * ldz + q);
+        *(uint4*)(sA0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
+      }
+      for (int e = tid; e < BM * CPR; e += NT) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (NN) {
+          const int kr = e >> 5, c = e & 31;
+          const int q = q0 + kr, n = col0 + c * 8;
+          if (q < r && n < N) v = *(const uint4*)(Rk + (size_t)q * N + n);
+          *(uint4*)(sB0 + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = v;
+        } else {
+          const int rl = e / CPR, c = e % CPR;
+          const int n = col0 + rl, q = q0 + c * 8;
+          if (n < N && q < r) v = *(const uint4*)(Rk + (size_t)n * r + q);
+          *(uint4*)(sB0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
+        }
+      }
+      __syncthreads();
+      const int left = (r - q0 + 15) / 16;
+      ext_compute(left < 2 ? left : 2);
+    }
+  }
+
+  // ---- output: through LDS, so that the tile leaves as 16 B per lane, 128 B per row segment.
+  // Each wave owns one 16 KiB stage array for its 128 x 64 sub-tile (row stride 128 B, chunk c
+  // of row m at c ^ ((m >> 1) & 7)); nothing is shared between waves after the barrier.
+  static_assert(WAVES_M == 2 && WAVES_N == 4 && TILE_BYTES == 16384, "epilogue layout assumes 2 x 4 waves");
+  __syncthreads();
+  char* ep = sA0;
+  if (wave == 1) ep = sA1;
+  if (wave == 2) ep = sA2;
+  if (wave == 3) ep = sA3;
+  if (wave == 4) ep = sB0;
+  if (wave == 5) ep = sB1;
+  if (wave == 6) ep = sB2;
+  if (wave == 7) ep = sB3;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16>(acc[i][j][4 * g + e]);
+        const int m = 32 * i + l32, c = 4 * j + g;
+        *(bf16x4*)(ep + m * 128 + ((c ^ ((m >> 1) & 7)) << 4) + 8 * lhi) = o;
+      }
+#pragma unroll
+  for (int it = 0; it < 16; ++it) {
+    const int r = 8 * it + (lane >> 3), cp = lane & 7;
+    const int c = cp ^ ((r >> 1) & 7);
+    const uint4 v = *(const uint4*)(ep + r * 128 + cp * 16);
+    const int grow = row0 + wm * WM + r, gcol = col0 + wn * WN + c * 8;
+    if (grow < M && gcol < N) *(uint4*)(C + (size_t)grow * N + gcol) = v;
+  }
+}
+
+}  // namespace gemmk
+}  // namespace mlora

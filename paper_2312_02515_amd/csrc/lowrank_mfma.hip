@@ -8,36 +8,20 @@
 //                  dB_k = Z^T dy_k          (Eq. "grad_lora", right)
 //
 // One launch covers all tasks: a block finds its task from the split positions.
-// Tiles are staged with direct global->LDS loads (16 B per lane) into a double
-// buffer; operands whose contraction index is not contiguous in memory (A_k, and
+// Tiles are staged with direct global->LDS loads (16 B per lane) into a 4-stage
+// ring, three tiles in flight per block (an HBM-bound stream needs tens of KiB in
+// flight per CU); operands whose contraction index is not contiguous in memory (A_k, and
 // everything in the two gradient products, where the contraction runs over
 // tokens) are read from LDS with the transposing ds_read_b64_tr_b16.
+#include "mfma_staging.h"
 #include "mlora_common.h"
 
 namespace mlora {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short short4v;
-typedef __attribute__((ext_vector_type(8))) short short8v;
+using namespace stage;
 
-#define AS1 __attribute__((address_space(1)))
-#define AS3 __attribute__((address_space(3)))
-
-__device__ __forceinline__ void load_lds_16B(const void* g, char* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const AS1 void*)g, (AS3 void*)lds_wave_base, 16, 0, 0);
-}
-
-__device__ __forceinline__ short4v lds_read_tr(const char* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((AS3 short4v*)p);
-}
-
-__device__ __forceinline__ bf16x8 join(short4v lo, short4v hi) {
-  short8v v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
+constexpr int NS = 4;  // stages of the LDS ring
 
 // ------------------------------------------------------------------------------------------
 // Out[i, 0:ldz] = s_k * In[i, :] * M_k   for the rows i of task k; columns >= r_k are zero.
@@ -52,9 +36,15 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ I
   constexpr int SBYTES = NQ * 32 * 128;
   __shared__ __attribute__((aligned(1024))) char sX0[TM * 128];
   __shared__ __attribute__((aligned(1024))) char sX1[TM * 128];
+  __shared__ __attribute__((aligned(1024))) char sX2[TM * 128];
+  __shared__ __attribute__((aligned(1024))) char sX3[TM * 128];
   // 64 zero bytes behind each small-operand tile: where lanes beyond the tile's columns point
   __shared__ __attribute__((aligned(1024))) char sS0[SBYTES + 64];
   __shared__ __attribute__((aligned(1024))) char sS1[SBYTES + 64];
+  __shared__ __attribute__((aligned(1024))) char sS2[SBYTES + 64];
+  __shared__ __attribute__((aligned(1024))) char sS3[SBYTES + 64];
+  char* const sX[NS] = {sX0, sX1, sX2, sX3};
+  char* const sS[NS] = {sS0, sS1, sS2, sS3};
 
   int b = blockIdx.x, k = 0;
   for (; k < st.K; ++k) {
@@ -72,8 +62,8 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ I
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (tid < 16) {
-    reinterpret_cast<int*>(sS0 + SBYTES)[tid] = 0;
-    reinterpret_cast<int*>(sS1 + SBYTES)[tid] = 0;
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) reinterpret_cast<int*>(sS[s_] + SBYTES)[tid] = 0;
   }
 
   const bf16* xptr[4];
@@ -89,7 +79,9 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ I
   const bf16* sptr[NQ];
 #pragma unroll
   for (int it = 0; it < NQ; ++it) {
-    const int piece = wave + 4 * it;
+    // pieces beyond the operand's rank re-fetch piece 0 into their own (never read) slot, so
+    // that every wave issues the same number of loads per tile
+    const int piece = (wave + 4 * it) < pieces ? (wave + 4 * it) : 0;
     if (SMALL_KMAJOR) {
       sptr[it] = Mk + piece * 512 + lane * 8;
     } else {
@@ -105,11 +97,9 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ I
 #pragma unroll
     for (int it = 0; it < 4; ++it) load_lds_16B(xptr[it] + (size_t)kt * 64, sx + (wave + 4 * it) * 1024);
 #pragma unroll
-    for (int it = 0; it < NQ; ++it) {
-      const int piece = wave + 4 * it;
-      if (piece < pieces) load_lds_16B(sptr[it] + (size_t)kt * sstep, ss + piece * 1024);
-    }
+    for (int it = 0; it < NQ; ++it) load_lds_16B(sptr[it] + (size_t)kt * sstep, ss + (wave + 4 * it) * 1024);
   };
+  constexpr int PER_TILE = 4 + NQ;
 
   const int l32 = lane & 31, lhi = lane >> 5;
   const int fsw = (l32 >> 1) & 7;
@@ -147,18 +137,29 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ I
     }
   };
 
+  // NS-stage ring, one barrier per tile: before tile kt is read, this wave's loads of tile kt
+  // have landed (the loads of the NS-2 younger tiles may stay in flight); the barrier then makes
+  // every wave's part of tile kt visible and tells that all waves are done with tile kt-1,
+  // whose stage is refilled next.
   const int KT = inner / 64;
-  issue(0, sX0, sS0);
-  for (int kt = 0; kt < KT; kt += 2) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < KT) issue(kt + 1, sX1, sS1);
-    compute(sX0, sS0);
-    if (kt + 1 >= KT) break;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 2 < KT) issue(kt + 2, sX0, sS0);
-    compute(sX1, sS1);
+  __syncthreads();  // the zero pads
+#pragma unroll
+  for (int s_ = 0; s_ < NS - 1; ++s_)
+    if (s_ < KT) issue(s_, sX[s_], sS[s_]);
+  for (int kt0 = 0; kt0 < KT; kt0 += NS) {
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) {
+      const int kt = kt0 + s_;
+      if (kt < KT) {
+        if (kt + NS - 2 < KT)
+          wait_vmcnt<(NS - 2) * PER_TILE>();
+        else
+          wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (kt + NS - 1 < KT) issue(kt + NS - 1, sX[(s_ + NS - 1) % NS], sS[(s_ + NS - 1) % NS]);
+        compute(sX[s_], sS[s_]);
+      }
+    }
   }
 
   // lane holds row m = 32*wave + l32 and columns q = 32j + 8g + 4*lhi + 0..3
@@ -196,9 +197,15 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
   constexpr int SBYTES = NQ * 32 * 128;  // 64 tokens x ldz x 2 B, ldz <= 32 NQ
   __shared__ __attribute__((aligned(1024))) char sB0[64 * WC * 2];
   __shared__ __attribute__((aligned(1024))) char sB1[64 * WC * 2];
+  __shared__ __attribute__((aligned(1024))) char sB2[64 * WC * 2];
+  __shared__ __attribute__((aligned(1024))) char sB3[64 * WC * 2];
   // 64 zero bytes behind each small-operand tile: where lanes beyond the tile's columns point
   __shared__ __attribute__((aligned(1024))) char sS0[SBYTES + 64];
   __shared__ __attribute__((aligned(1024))) char sS1[SBYTES + 64];
+  __shared__ __attribute__((aligned(1024))) char sS2[SBYTES + 64];
+  __shared__ __attribute__((aligned(1024))) char sS3[SBYTES + 64];
+  char* const sB[NS] = {sB0, sB1, sB2, sB3};
+  char* const sS[NS] = {sS0, sS1, sS2, sS3};
 
   const int k = blockIdx.x / chunks, ch = blockIdx.x % chunks;
   const int col0 = ch * WC;
@@ -208,8 +215,8 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (tid < 16) {
-    reinterpret_cast<int*>(sS0 + SBYTES)[tid] = 0;
-    reinterpret_cast<int*>(sS1 + SBYTES)[tid] = 0;
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) reinterpret_cast<int*>(sS[s_] + SBYTES)[tid] = 0;
   }
 
   // Big tile: 64 token rows x 256 B; wave instruction w covers rows 4w..4w+3
@@ -229,10 +236,14 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
   int srow[NQ], scol[NQ];
 #pragma unroll
   for (int it = 0; it < NQ; ++it) {
-    const int chunk = (wave + 4 * it) * 64 + lane;
+    // pieces beyond the tile re-fetch piece 0 into their own (never read) slot, so that every
+    // wave issues the same number of loads per tile
+    const int piece = (wave + 4 * it) < pieces ? (wave + 4 * it) : 0;
+    const int chunk = piece * 64 + lane;
     srow[it] = chunk / cpr;
     scol[it] = (chunk % cpr) * 8;
   }
+  constexpr int PER_TILE = 4 + NQ;
 
   auto issue = [&](int kt, char* sb, char* ss) {
     const int t0 = lo + kt * 64;
@@ -244,12 +255,9 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
     }
 #pragma unroll
     for (int it = 0; it < NQ; ++it) {
-      const int piece = wave + 4 * it;
-      if (piece < pieces) {
-        int tok = t0 + srow[it];
-        tok = tok < T ? tok : T - 1;
-        load_lds_16B(Small + (size_t)tok * ldz + scol[it], ss + piece * 1024);
-      }
+      int tok = t0 + srow[it];
+      tok = tok < T ? tok : T - 1;
+      load_lds_16B(Small + (size_t)tok * ldz + scol[it], ss + (wave + 4 * it) * 1024);
     }
   };
 
@@ -299,22 +307,24 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
   };
 
   const int KT = (tk + 63) / 64;
-  if (KT > 0) issue(0, sB0, sS0);
-  for (int kt = 0; kt < KT; kt += 2) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < KT) issue(kt + 1, sB1, sS1);
-    {
-      const int left = tk - kt * 64;
-      compute(sB0, sS0, left < 64 ? left : 64);
-    }
-    if (kt + 1 >= KT) break;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 2 < KT) issue(kt + 2, sB0, sS0);
-    {
-      const int left = tk - (kt + 1) * 64;
-      compute(sB1, sS1, left < 64 ? left : 64);
+  __syncthreads();  // the zero pads
+#pragma unroll
+  for (int s_ = 0; s_ < NS - 1; ++s_)
+    if (s_ < KT) issue(s_, sB[s_], sS[s_]);
+  for (int kt0 = 0; kt0 < KT; kt0 += NS) {
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) {
+      const int kt = kt0 + s_;
+      if (kt < KT) {
+        if (kt + NS - 2 < KT)
+          wait_vmcnt<(NS - 2) * PER_TILE>();
+        else
+          wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (kt + NS - 1 < KT) issue(kt + NS - 1, sB[(s_ + NS - 1) % NS], sS[(s_ + NS - 1) % NS]);
+        const int left = tk - kt * 64;
+        compute(sB[s_], sS[s_], left < 64 ? left : 64);
+      }
     }
   }
 
