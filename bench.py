@@ -38,6 +38,48 @@ def _traffic_bytes_per_launch():
         return None
 
 
+def sample_power(run_steps, seconds=2.0):
+    """Socket power and shader clock while the hot path runs (outside the timed region): keeps
+    launching steps for `seconds` while a thread polls `amd-smi metric -p -c`.  Returns None if
+    amd-smi is not available.  Context for the roofline: at the board's power cap the matrix
+    cores run below the 2.4 GHz the published peak assumes."""
+    import re
+    import shutil
+    import subprocess
+    import threading
+    import torch
+    if shutil.which("amd-smi") is None:
+        return None
+    samples, stop = [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                out = subprocess.run(["amd-smi", "metric", "-p", "-c"], capture_output=True, text=True, timeout=10).stdout
+            except Exception:
+                return
+            pw = re.search(r"SOCKET_POWER:\s*([0-9.]+)\s*W", out)
+            gfx = out.split("GFX_0:")[1] if "GFX_0:" in out else ""
+            clks = [float(x) for x in re.findall(r"\n\s+CLK:\s*([0-9.]+)\s*MHz", gfx)[:8]]
+            if pw and clks:
+                samples.append((float(pw.group(1)), sum(clks) / len(clks)))
+
+    th = threading.Thread(target=poll, daemon=True)
+    th.start()
+    t_end = time.perf_counter() + seconds
+    while time.perf_counter() < t_end:
+        run_steps()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join(timeout=15)
+    samples = samples[1:] if len(samples) > 1 else samples  # the first poll may predate the load
+    if not samples:
+        return None
+    return {"socket_power_w": sum(p for p, _ in samples) / len(samples),
+            "gfx_clock_mhz": sum(c for _, c in samples) / len(samples), "samples": len(samples),
+            "source": "amd-smi metric -p -c, polled while the step loop runs after the timed region"}
+
+
 def cpu_baseline(wl_mod, w, tokens_per_adapter, seed):
     """Time the oracle (as it stands) on the first `tokens_per_adapter` tokens of every adapter,
     all seven projections, forward + backward."""
@@ -73,10 +115,11 @@ def cpu_baseline(wl_mod, w, tokens_per_adapter, seed):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-tokens", type=int, default=384, help="tokens per adapter in the CPU oracle sample (0 = skip)")
+    ap.add_argument("--no-power", action="store_true", help="skip the amd-smi power/clock sample after the timed region")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that calibrates the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
@@ -150,6 +193,8 @@ def main():
                      "share_of_step_time": gemm_ms / args.steps / ms_per_step,
                      "traffic": _traffic_bytes_per_launch()},
     }
+    if not args.no_power:
+        out["power"] = sample_power(step)
     if args.cpu_tokens > 0:
         out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_tokens, args.seed)
     print(json.dumps(out), flush=True)
