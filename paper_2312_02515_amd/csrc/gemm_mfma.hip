@@ -87,10 +87,10 @@ hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int K
     }
   }
   if (nn)
-    hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, true, 4>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
+    hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, true, 64>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
                        tiles_m, tiles_n);
   else
-    hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, false, 4>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
+    hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, false, 64>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
                        tiles_m, tiles_n);
   const hipError_t err = hipGetLastError();
   if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], stream);

@@ -4,14 +4,14 @@
 //     NN = true  (forward,  Eq. "forward"):      Bm = W [Kd,N] (contraction index = rows of W),  R_k = B_k [r_k, N]
 //     NN = false (backward, Eq. "grad_output"):  Bm = W [N,Kd] (contraction index = columns),     R_k = A_k [N, r_k]
 //
-// Tile 256 x 256 x 32, 8 waves (2 x 4, wave tile 128 x 64), fp32 accumulation in
-// v_mfma_f32_32x32x16_bf16 with the accumulators in AccVGPRs, 4-stage ring of LDS tiles filled by
-// direct global->LDS loads (global_load_lds_dwordx4, 16 B per lane).  A wave-wide direct load
+// Tile 256 x 256 x BK, 8 waves (2 x 4, wave tile 128 x 64), fp32 accumulation in
+// v_mfma_f32_32x32x16_bf16 with the accumulators in AccVGPRs, LDS tiles (BK = 64) filled by
+// direct global->LDS loads (global_load_lds_dwordx4, 16 B per lane) into a double buffer.  A wave-wide direct load
 // fills 1 KiB of contiguous LDS, so the bank-conflict swizzle is applied by choosing which global
 // 16-byte chunk each lane fetches:
-//   * K-contiguous tiles (A, and Bm when !NN): 256 rows x 64 B; chunk c of row r sits at chunk
-//     position c ^ ((r >> 2) & 3); read with ds_read_b128.
-//   * Bm when NN: 32 contraction rows x 512 B; chunk c of row k sits at c ^ ((k & 3) << 2); read
+//   * K-contiguous tiles (A, and Bm when !NN): 256 rows x 128 B; chunk c of row r sits at chunk
+//     position c ^ ((r >> 1) & 7); read with ds_read_b128.
+//   * Bm when NN: BK contraction rows x 512 B; chunk c of row k sits at c ^ ((k & 3) << 2); read
 //     with ds_read_b64_tr_b16, which hands each lane four consecutive contraction indices of one
 //     output column -- no transposed copy of W is ever made.
 // The MFMA takes the weight fragment as its first operand so that each lane ends up with four
@@ -30,25 +30,28 @@ using namespace stage;
 constexpr int BM = 256, BN = 256;
 
 // ------------------------------------------------------------------------------------------
-// Schedule: contraction tiles of 32, NS-stage ring (NS = 4 or 5), and every memory
-// instruction placed between two MFMAs.  Issuing a vector-memory load keeps
-// the SIMD's issue port busy for some cycles; when a wave issues its loads back to back the
-// matrix pipe idles meanwhile, when each load follows an MFMA it hides behind that MFMA's
-// 32 cycles.  The same holds for the LDS fragment reads, which are issued one MFMA step ahead
-// of their use (two register sets of fragments).
-//   iteration kt (two MFMA steps):
-//     step 0: MFMAs on the fragments of (tile kt, step 0); between them: LDS reads of (kt, step 1)
-//             and the direct-to-LDS loads of tile kt+NS-1
-//     step 1: MFMAs on (kt, step 1); between them: LDS reads of (kt+1, step 0)
-//     s_waitcnt so that this wave's loads of tile kt+2 have landed; barrier
-//   so at the barrier that ends iteration kt every wave has finished reading tile kt (its stage
-//   is refilled during iteration kt+1) and tile kt+2 is visible to all (read from kt+1 on).
+// Schedule.  Contraction tiles of 64 (rows of 128 B, so every request to the L2 is a full cache
+// line), double-buffered in LDS; tile kt+1 is fetched while tile kt is computed.  Every memory
+// instruction sits between two MFMAs: issuing a vector-memory load keeps the SIMD's issue port
+// busy for some cycles; when a wave issues its loads back to back the matrix pipe idles
+// meanwhile, when each load follows an MFMA it hides behind that MFMA's 32 cycles.  The same
+// holds for the LDS fragment reads, which run one MFMA step ahead of their use (two register
+// sets of fragments); only the first fragments of a tile are read right after the barrier
+// (their latency is covered by the other wave of the SIMD).
+//   tile kt:  s_waitcnt vmcnt(0); barrier            (tile kt visible, tile kt-1's stage free)
+//             step 0: MFMAs on (kt, step 0); behind them LDS reads of (kt, step 1) and the 8
+//                     direct-to-LDS loads of tile kt+1
+//             steps 1..3: MFMAs on (kt, step s); behind them LDS reads of (kt, step s+1)
+// Contraction tiles of 32 in a 4- or 5-stage ring (deeper prefetch, half-line requests) were
+// measured 7 % slower on the K-contiguous operands and equal on the forward's W tile.
 // ------------------------------------------------------------------------------------------
-template <int WAVES_M, int WAVES_N, bool NN, int NS>
+template <int WAVES_M, int WAVES_N, bool NN, int BK>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
     const bf16* __restrict__ A, const bf16* __restrict__ Bm, bf16* __restrict__ C, int M, int N, int Kd,
     const bf16* __restrict__ L, int ldz, SegTable st, PtrTable R, int tiles_m, int tiles_n) {
-  constexpr int BK = 32;
+  static_assert(BK == 64, "contraction tile");
+  constexpr int NS = 2;                        // LDS stages: 2 x (32 + 32) KiB
+  constexpr int KS = BK / 16;                  // MFMA steps per contraction tile
   constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int FM = WM / 32, FN = WN / 32;
@@ -56,24 +59,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
   constexpr int NOPS = FM + FN;                // fragment reads per step
   constexpr int RSLOTS = (NOPS + 1) / 2;       // two fragment reads behind each of the first MFMAs
   constexpr int ROWB = BK * 2, CPR = BK / 8, RW = 256 / ROWB, RPI = 1024 / ROWB;
-  constexpr int TILE_BYTES = BM * ROWB;        // 16 KiB; the NN weight tile (32 x 512 B) has the same size
+  constexpr int TILE_BYTES = BM * ROWB;        // the NN weight tile (BK x 512 B) has the same size
   constexpr int LPW = TILE_BYTES / 1024 / NW;  // wave-wide loads per wave per operand tile
   constexpr int PER_TILE = 2 * LPW;
-  static_assert(NS == 4 || NS == 5, "ring depth");
-  static_assert(RSLOTS + PER_TILE <= NMF, "not enough MFMAs per step to hide the memory instructions");
+  static_assert(PER_TILE <= NMF && RSLOTS <= NMF, "not enough MFMAs per step to hide the memory instructions");
 
   __shared__ __attribute__((aligned(1024))) char sA0[TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) char sA1[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sA2[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sA3[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sA4[NS > 4 ? TILE_BYTES : 16];
   __shared__ __attribute__((aligned(1024))) char sB0[TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) char sB1[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sB2[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sB3[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sB4[NS > 4 ? TILE_BYTES : 16];
-  char* const sA[5] = {sA0, sA1, sA2, sA3, sA4};
-  char* const sB[5] = {sB0, sB1, sB2, sB3, sB4};
+  char* const sA[2] = {sA0, sA1};
+  char* const sB[2] = {sB0, sB1};
 
   const int total = tiles_m * tiles_n;
   const int bid = blockIdx.x;
@@ -195,35 +191,25 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
     }
   };
 
+  // ---- main contraction loop (unrolled by the two stages so that stage addresses are constants)
+  static_assert(NS == 2 && KS == 4, "loop below is written for a double buffer of 4-step tiles");
   const int KT = Kd / BK;
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < KT) {
+  for (int idx = 0; idx < PER_TILE; ++idx) issue_one(0, idx, sA[0], sB[0]);
+  for (int kt0 = 0; kt0 < KT; kt0 += 2) {
 #pragma unroll
-      for (int idx = 0; idx < PER_TILE; ++idx) issue_one(s, idx, sA[s], sB[s]);
-    }
-  // tiles 0 and 1 landed (younger tiles may still be in flight)
-  if (KT >= NS - 1)
-    wait_vmcnt<(NS - 3) * PER_TILE>();
-  else
-    wait_vmcnt<0>();
-  __builtin_amdgcn_s_barrier();
-#pragma unroll
-  for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
-
-  for (int kt0 = 0; kt0 < KT; kt0 += NS) {
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
+    for (int s = 0; s < 2; ++s) {
       const int kt = kt0 + s;
       if (kt < KT) {
-        const bool ld = kt + NS - 1 < KT;
-        step(0, true, sA[s], sB[s], 1, ld, kt + NS - 1, sA[(s + NS - 1) % NS], sB[(s + NS - 1) % NS]);
-        step(1, kt + 1 < KT, sA[(s + 1) % NS], sB[(s + 1) % NS], 0, false, 0, nullptr, nullptr);
-        if (ld)  // every tile up to kt+NS-1 has been issued: tiles kt+3.. may stay in flight
-          wait_vmcnt<(NS - 3) * PER_TILE>();
-        else
-          wait_vmcnt<0>();
+        wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int op = 0; op < NOPS; ++op) read_op(sA[s], sB[s], 0, op, af[0], bfr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        step(0, true, sA[s], sB[s], 1, kt + 1 < KT, kt + 1, sA[s ^ 1], sB[s ^ 1]);
+        step(1, true, sA[s], sB[s], 2, false, 0, nullptr, nullptr);
+        step(0, true, sA[s], sB[s], 3, false, 0, nullptr, nullptr);
+        step(1, false, nullptr, nullptr, 0, false, 0, nullptr, nullptr);
       }
     }
   }
@@ -232,7 +218,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
   // passed the last barrier after its last fragment read)
   auto ext_compute = [&](int ksteps) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       if (ks < ksteps) {
 #pragma unroll
         for (int op = 0; op < NOPS; ++op) read_op(sA0, sB0, ks, op, af[0], bfr[0]);
@@ -276,23 +262,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
       }
       __syncthreads();
       const int left = (r - q0 + 15) / 16;
-      ext_compute(left < 2 ? left : 2);
+      ext_compute(left < KS ? left : KS);
     }
   }
 
   // ---- output: through LDS, so that the tile leaves as 16 B per lane, 128 B per row segment.
   // Each wave owns one 16 KiB stage array for its 128 x 64 sub-tile (row stride 128 B, chunk c
   // of row m at c ^ ((m >> 1) & 7)); nothing is shared between waves after the barrier.
-  static_assert(WAVES_M == 2 && WAVES_N == 4 && TILE_BYTES == 16384, "epilogue layout assumes 2 x 4 waves");
+  static_assert(WAVES_M == 2 && WAVES_N == 4, "epilogue layout assumes 2 x 4 waves");
   __syncthreads();
   char* ep = sA0;
-  if (wave == 1) ep = sA1;
-  if (wave == 2) ep = sA2;
-  if (wave == 3) ep = sA3;
-  if (wave == 4) ep = sB0;
-  if (wave == 5) ep = sB1;
-  if (wave == 6) ep = sB2;
-  if (wave == 7) ep = sB3;
+  if (wave >> 1 == 1) ep = sA1;  // four stage arrays of 32 KiB, two waves each
+  if (wave >> 1 == 2) ep = sB0;
+  if (wave >> 1 == 3) ep = sB1;
+  ep += (wave & 1) * 16384;
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
