@@ -36,12 +36,14 @@ constexpr int BM = 256, BN = 256;
 // busy for some cycles; when a wave issues its loads back to back the matrix pipe idles
 // meanwhile, when each load follows an MFMA it hides behind that MFMA's 32 cycles.  The same
 // holds for the LDS fragment reads, which run one MFMA step ahead of their use (two register
-// sets of fragments); only the first fragments of a tile are read right after the barrier
-// (their latency is covered by the other wave of the SIMD).
-//   tile kt:  s_waitcnt vmcnt(0); barrier            (tile kt visible, tile kt-1's stage free)
-//             step 0: MFMAs on (kt, step 0); behind them LDS reads of (kt, step 1) and the 8
-//                     direct-to-LDS loads of tile kt+1
-//             steps 1..3: MFMAs on (kt, step s); behind them LDS reads of (kt, step s+1)
+// sets of fragments).
+//   tile kt:  steps 0..2: MFMAs on (kt, step s); behind them LDS reads of (kt, step s+1)
+//             s_waitcnt vmcnt(0), lgkmcnt(0); barrier   (tile kt+1 visible; every wave holds its
+//                     last fragments of tile kt in registers, so tile kt's stage is free)
+//             step 3: MFMAs on (kt, step 3); behind them LDS reads of (kt+1, step 0) and the 8
+//                     direct-to-LDS loads of tile kt+2 into tile kt's stage
+// The barrier sits in the middle of the MFMA stream with the next step's fragments already in
+// registers, so no LDS read latency is exposed behind it.
 // Contraction tiles of 32 in a 4- or 5-stage ring (deeper prefetch, half-line requests) were
 // measured 7 % slower on the K-contiguous operands and equal on the forward's W tile.
 // ------------------------------------------------------------------------------------------
@@ -196,20 +198,30 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
   const int KT = Kd / BK;
 #pragma unroll
   for (int idx = 0; idx < PER_TILE; ++idx) issue_one(0, idx, sA[0], sB[0]);
+  if (KT > 1) {
+#pragma unroll
+    for (int idx = 0; idx < PER_TILE; ++idx) issue_one(1, idx, sA[1], sB[1]);
+    wait_vmcnt<PER_TILE>();
+  } else {
+    wait_vmcnt<0>();
+  }
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
+  __builtin_amdgcn_sched_barrier(0);
   for (int kt0 = 0; kt0 < KT; kt0 += 2) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const int kt = kt0 + s;
       if (kt < KT) {
-        wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-#pragma unroll
-        for (int op = 0; op < NOPS; ++op) read_op(sA[s], sB[s], 0, op, af[0], bfr[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        step(0, true, sA[s], sB[s], 1, kt + 1 < KT, kt + 1, sA[s ^ 1], sB[s ^ 1]);
+        step(0, true, sA[s], sB[s], 1, false, 0, nullptr, nullptr);
         step(1, true, sA[s], sB[s], 2, false, 0, nullptr, nullptr);
         step(0, true, sA[s], sB[s], 3, false, 0, nullptr, nullptr);
-        step(1, false, nullptr, nullptr, 0, false, 0, nullptr, nullptr);
+        // tile kt+1 has landed (this wave's part), every fragment of tile kt is in registers
+        wait_vmcnt<0>();
+        wait_lds();
+        __builtin_amdgcn_s_barrier();
+        step(1, kt + 1 < KT, sA[s ^ 1], sB[s ^ 1], 0, kt + 2 < KT, kt + 2, sA[s], sB[s]);
       }
     }
   }
@@ -266,16 +278,22 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
     }
   }
 
-  // ---- output: through LDS, so that the tile leaves as 16 B per lane, 128 B per row segment.
-  // Each wave owns one 16 KiB stage array for its 128 x 64 sub-tile (row stride 128 B, chunk c
-  // of row m at c ^ ((m >> 1) & 7)); nothing is shared between waves after the barrier.
-  static_assert(WAVES_M == 2 && WAVES_N == 4, "epilogue layout assumes 2 x 4 waves");
+  // ---- output: through LDS, so that the tile leaves as 16 B per lane in full row segments of
+  // the wave's sub-tile.  Each wave owns WM x WN x 2 bytes of the stage arrays (row stride WN x 2
+  // bytes, chunk c of row m at c ^ swizzle(m)); nothing is shared between waves after the barrier.
+  constexpr int OCH = WN / 8;                 // 16-byte chunks per output row of the wave's sub-tile
+  constexpr int OROWB = WN * 2;               // bytes per such row
+  constexpr int ORPI = 64 / OCH;              // rows per wave-wide store
+  constexpr int WBYTES = WM * OROWB;          // bytes per wave
+  static_assert(NW * WBYTES == 4 * TILE_BYTES && (TILE_BYTES % WBYTES) == 0, "sub-tiles must tile the stage arrays");
+  constexpr int WPA = TILE_BYTES / WBYTES;    // waves per stage array
+  auto oswz = [](int m) { return OCH == 8 ? ((m >> 1) & 7) : (m & (OCH - 1)); };
   __syncthreads();
   char* ep = sA0;
-  if (wave >> 1 == 1) ep = sA1;  // four stage arrays of 32 KiB, two waves each
-  if (wave >> 1 == 2) ep = sB0;
-  if (wave >> 1 == 3) ep = sB1;
-  ep += (wave & 1) * 16384;
+  if (wave / WPA == 1) ep = sA1;
+  if (wave / WPA == 2) ep = sB0;
+  if (wave / WPA == 3) ep = sB1;
+  ep += (wave % WPA) * WBYTES;
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -286,13 +304,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16>(acc[i][j][4 * g + e]);
         const int m = 32 * i + l32, c = 4 * j + g;
-        *(bf16x4*)(ep + m * 128 + ((c ^ ((m >> 1) & 7)) << 4) + 8 * lhi) = o;
+        *(bf16x4*)(ep + m * OROWB + ((c ^ oswz(m)) << 4) + 8 * lhi) = o;
       }
 #pragma unroll
-  for (int it = 0; it < 16; ++it) {
-    const int r = 8 * it + (lane >> 3), cp = lane & 7;
-    const int c = cp ^ ((r >> 1) & 7);
-    const uint4 v = *(const uint4*)(ep + r * 128 + cp * 16);
+  for (int it = 0; it < WM / ORPI; ++it) {
+    const int r = ORPI * it + lane / OCH, cp = lane % OCH;
+    const int c = cp ^ oswz(r);
+    const uint4 v = *(const uint4*)(ep + r * OROWB + cp * 16);
     const int grow = row0 + wm * WM + r, gcol = col0 + wn * WN + c * 8;
     if (grow < M && gcol < N) *(uint4*)(C + (size_t)grow * N + gcol) = v;
   }

@@ -26,12 +26,13 @@ using namespace stage;
 // Out[i, 0:ldz] = s_k * In[i, :] * M_k   for the rows i of task k; columns >= r_k are zero.
 //   SMALL_KMAJOR = true : M_k = A_k  [inner, r_k]  (rows of A_k are contraction indices)
 //   SMALL_KMAJOR = false: M_k = B_k^T, B_k [r_k, inner]
-// Block: 128 rows of one task, 4 waves x 32 rows, contraction tiles of 64.
+// Block: TM rows of one task (TM = 32, 64 or 128), one wave per 32 rows, contraction tiles of 64.
 // ------------------------------------------------------------------------------------------
-template <bool SMALL_KMAJOR, int NQ, int NS>
-__global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ In, int inner,
-                                                      bf16* __restrict__ Out, int ldz, SegTable st, PtrTable Mp) {
-  constexpr int TM = 128;
+template <bool SMALL_KMAJOR, int NQ, int NS, int TM>
+__global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const bf16* __restrict__ In, int inner,
+                                                         bf16* __restrict__ Out, int ldz, SegTable st, PtrTable Mp) {
+  constexpr int NWV = TM / 32;                     // waves per block
+  constexpr int SPW = (4 * NQ + NWV - 1) / NWV;    // 1 KiB pieces of the small operand per wave
   constexpr int SBYTES = NQ * 32 * 128;
   __shared__ __attribute__((aligned(1024))) char sX0[TM * 128];
   __shared__ __attribute__((aligned(1024))) char sX1[TM * 128];
@@ -69,19 +70,19 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ I
   const bf16* xptr[4];
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
-    const int rl = 8 * (wave + 4 * it) + (lane >> 3);
+    const int rl = 8 * (wave + NWV * it) + (lane >> 3);
     const int c = (lane & 7) ^ ((rl >> 1) & 7);
     int row = lo + rl;
     row = row < hi ? row : hi - 1;
     xptr[it] = In + (size_t)row * inner + c * 8;
   }
   const int pieces = r / 8;  // 1 KiB pieces of the small operand's tile
-  const bf16* sptr[NQ];
+  const bf16* sptr[SPW];
 #pragma unroll
-  for (int it = 0; it < NQ; ++it) {
+  for (int it = 0; it < SPW; ++it) {
     // pieces beyond the operand's rank re-fetch piece 0 into their own (never read) slot, so
     // that every wave issues the same number of loads per tile
-    const int piece = (wave + 4 * it) < pieces ? (wave + 4 * it) : 0;
+    const int piece = (wave + NWV * it) < pieces ? (wave + NWV * it) : 0;
     if (SMALL_KMAJOR) {
       sptr[it] = Mk + piece * 512 + lane * 8;
     } else {
@@ -95,11 +96,14 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma(const bf16* __restrict__ I
 
   auto issue = [&](int kt, char* sx, char* ss) {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) load_lds_16B(xptr[it] + (size_t)kt * 64, sx + (wave + 4 * it) * 1024);
+    for (int it = 0; it < 4; ++it) load_lds_16B(xptr[it] + (size_t)kt * 64, sx + (wave + NWV * it) * 1024);
 #pragma unroll
-    for (int it = 0; it < NQ; ++it) load_lds_16B(sptr[it] + (size_t)kt * sstep, ss + (wave + 4 * it) * 1024);
+    for (int it = 0; it < SPW; ++it)
+      if (wave + NWV * it < 4 * NQ) load_lds_16B(sptr[it] + (size_t)kt * sstep, ss + (wave + NWV * it) * 1024);
   };
-  constexpr int PER_TILE = 4 + NQ;
+  // loads per wave per tile; the same for every wave when NWV divides 4 NQ (it always does here)
+  static_assert((4 * NQ) % NWV == 0, "small-operand pieces must split evenly over the waves");
+  constexpr int PER_TILE = 4 + SPW;
 
   const int l32 = lane & 31, lhi = lane >> 5;
   const int fsw = (l32 >> 1) & 7;
@@ -372,15 +376,21 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
 // so two blocks share a CU; measured 8 % faster than four stages with one block per CU.
 constexpr int kRing = 3;
 
-template <bool KMAJOR>
-void launch_rows(int nq, dim3 grid, hipStream_t s, const bf16* In, int inner, bf16* Out, int ldz, const SegTable& st,
-                 const PtrTable& M) {
+template <bool KMAJOR, int TM, int NS>
+void launch_rows_tm(int nq, dim3 grid, hipStream_t s, const bf16* In, int inner, bf16* Out, int ldz, const SegTable& st,
+                    const PtrTable& M) {
   if (nq == 1)
-    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 1, kRing>), grid, dim3(256), 0, s, In, inner, Out, ldz, st, M);
+    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 1, NS, TM>), grid, dim3(TM * 2), 0, s, In, inner, Out, ldz, st, M);
   else if (nq == 2)
-    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 2, kRing>), grid, dim3(256), 0, s, In, inner, Out, ldz, st, M);
+    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 2, NS, TM>), grid, dim3(TM * 2), 0, s, In, inner, Out, ldz, st, M);
   else
-    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 4, kRing>), grid, dim3(256), 0, s, In, inner, Out, ldz, st, M);
+    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 4, NS, TM>), grid, dim3(TM * 2), 0, s, In, inner, Out, ldz, st, M);
+}
+
+int row_blocks(const SegTable& st, int tm) {
+  int blocks = 0;
+  for (int k = 0; k < st.K; ++k) blocks += (st.off[k + 1] - st.off[k] + tm - 1) / tm;
+  return blocks;
 }
 
 template <bool WIDE_FIRST>
@@ -404,13 +414,26 @@ int nq_of(int ldz) { return ldz <= 32 ? 1 : (ldz <= 64 ? 2 : 4); }
 // Z = s x A (a_major = true, M = A_k) or G = s dy B^T (a_major = false, M = B_k).
 hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* Out, const PtrTable& M,
                              bool a_major) {
-  int blocks = 0;
-  for (int k = 0; k < c.K; ++k) blocks += (c.st.off[k + 1] - c.st.off[k] + 127) / 128;
+  // the largest row tile that still gives every CU (256) a block: at equal block counts the
+  // larger tile is faster (fewer fetches of the small operand per row)
+  int tm = 128;
+  if (row_blocks(c.st, tm) < 256) tm = 64;
+  if (tm == 64 && row_blocks(c.st, tm) < 256) tm = 32;
+  const int blocks = row_blocks(c.st, tm);
   if (blocks == 0) return hipSuccess;
+  const int nq = nq_of(c.ldz);
+  const dim3 grid(blocks);
+#define MLORA_ROWS(KM)                                                                           \
+  do {                                                                                           \
+    if (tm == 128) launch_rows_tm<KM, 128, kRing>(nq, grid, c.stream, In, inner, Out, c.ldz, c.st, M);     \
+    else if (tm == 64) launch_rows_tm<KM, 64, kRing>(nq, grid, c.stream, In, inner, Out, c.ldz, c.st, M);  \
+    else launch_rows_tm<KM, 32, kRing>(nq, grid, c.stream, In, inner, Out, c.ldz, c.st, M);                \
+  } while (0)
   if (a_major)
-    launch_rows<true>(nq_of(c.ldz), dim3(blocks), c.stream, In, inner, Out, c.ldz, c.st, M);
+    MLORA_ROWS(true);
   else
-    launch_rows<false>(nq_of(c.ldz), dim3(blocks), c.stream, In, inner, Out, c.ldz, c.st, M);
+    MLORA_ROWS(false);
+#undef MLORA_ROWS
   return hipGetLastError();
 }
 

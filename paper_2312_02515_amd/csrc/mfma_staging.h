@@ -39,6 +39,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Waits until every LDS read this wave has issued has returned its data.
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 // ds_read_b64_tr_b16: within each group of 16 lanes, lane L supplies the address of 4 consecutive
 // 16-bit elements of row L / 4 (columns 4 (L % 4) ..); lane i receives column i of that 4 x 16
 // block, i.e. four consecutive rows of one column.
