@@ -120,6 +120,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-tokens", type=int, default=384, help="tokens per adapter in the CPU oracle sample (0 = skip)")
     ap.add_argument("--no-power", action="store_true", help="skip the amd-smi power/clock sample after the timed region")
+    ap.add_argument("--recompute", action="store_true",
+                    help="time the activation-recompute pair of entry points (nothing saved between forward and "
+                         "backward; the backward recomputes s x A) instead of the default pair")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that calibrates the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
@@ -144,12 +147,20 @@ def main():
         inp = wl.make_workload_inputs(w, pi, device=dev, seed=args.seed)
         prob = mb.Problem(w.T, p.h, p.d, inp.W, inp.seg_offsets, inp.ranks, inp.scalings, inp.A, inp.B)
         dA, dB = prob.alloc_grads()
-        projs.append(dict(p=p, inp=inp, prob=prob, saved=prob.alloc_saved(), ws=prob.alloc_workspace(),
+        projs.append(dict(p=p, inp=inp, prob=prob, saved=prob.alloc_saved(),
+                          ws=prob.alloc_recompute_workspace() if args.recompute else prob.alloc_workspace(),
                           Y=torch.empty((w.T, p.d), dtype=inp.X.dtype, device=dev),
                           dX=torch.empty((w.T, p.h), dtype=inp.X.dtype, device=dev), dA=dA, dB=dB))
     flops_step = sum(w.flops(p) for p in w.projections)
 
     def step():
+        if args.recompute:
+            for q in projs:
+                mb.mlora_lora_fwd_nosave(q["prob"], q["inp"].X, q["Y"], q["ws"], stream)
+            for q in reversed(projs):
+                mb.mlora_lora_bwd_recompute(q["prob"], q["inp"].X, q["inp"].dY, q["dX"], q["dA"], q["dB"], False,
+                                            q["ws"], stream)
+            return
         for q in projs:
             mb.mlora_lora_fwd(q["prob"], q["inp"].X, q["Y"], q["saved"], q["ws"], stream)
         for q in reversed(projs):
@@ -184,7 +195,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD, "tokens": w.T, "adapters": w.K, "ranks": list(w.ranks),
-                   "projections": [f"{p.name}:{p.h}x{p.d}" for p in w.projections], "seed": args.seed},
+                   "projections": [f"{p.name}:{p.h}x{p.d}" for p in w.projections], "seed": args.seed,
+                   "variant": "recompute" if args.recompute else "saved"},
         "tokens_per_s": w.T / (ms_per_step * 1e-3),
         "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "k_gemm_mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,

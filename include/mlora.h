@@ -120,6 +120,20 @@ mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* d
                             void* dX, float* const* dA, float* const* dB, int accumulate,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Activation-recompute variant of the pair above, for training runs that checkpoint activations
+ * (the single-GPU setup of section 4.1 does): nothing is kept between the two calls; the
+ * backward call recomputes s_k x_k A_k from X (one more pass over X, 2 t_k h r_k flops per task)
+ * instead of reading a `saved` buffer.  Results are bit-identical to mlora_lora_fwd /
+ * mlora_lora_bwd on the same inputs.  Both calls take a workspace of at least
+ * mlora_lora_recompute_workspace_bytes(p) bytes (0 if the problem is invalid), 256-byte
+ * aligned, scratch; every other argument is as in mlora_lora_fwd / mlora_lora_bwd. */
+size_t mlora_lora_recompute_workspace_bytes(const mlora_problem* p);
+mlora_status mlora_lora_fwd_nosave(const mlora_problem* p, const void* X, void* Y,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, const void* dY,
+                                      void* dX, float* const* dA, float* const* dB, int accumulate,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Plain text for a status code; never NULL. */
 const char* mlora_status_string(mlora_status s);
 

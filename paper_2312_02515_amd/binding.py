@@ -24,7 +24,8 @@ STATUS_NAMES = {0: "MLORA_OK", 1: "MLORA_ERR_NULL", 2: "MLORA_ERR_SHAPE", 3: "ML
                 4: "MLORA_ERR_RANK", 5: "MLORA_ERR_DTYPE", 6: "MLORA_ERR_WORKSPACE", 7: "MLORA_ERR_HIP"}
 
 EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_validate", "mlora_lora_fwd",
-           "mlora_lora_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_gemm",
+           "mlora_lora_bwd", "mlora_lora_recompute_workspace_bytes", "mlora_lora_fwd_nosave",
+           "mlora_lora_bwd_recompute", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_gemm",
            "mlora_profile_gemm_read"]
 
 
@@ -66,6 +67,15 @@ def _load() -> ctypes.CDLL:
     l.mlora_lora_bwd.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                  ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    l.mlora_lora_recompute_workspace_bytes.restype = ctypes.c_size_t
+    l.mlora_lora_recompute_workspace_bytes.argtypes = [pp]
+    l.mlora_lora_fwd_nosave.restype = ctypes.c_int
+    l.mlora_lora_fwd_nosave.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                        ctypes.c_void_p]
+    l.mlora_lora_bwd_recompute.restype = ctypes.c_int
+    l.mlora_lora_bwd_recompute.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                                           ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     l.mlora_status_string.restype = ctypes.c_char_p
     l.mlora_status_string.argtypes = [ctypes.c_int]
     l.mlora_last_hip_error.restype = ctypes.c_int
@@ -121,6 +131,12 @@ class Problem:
     def workspace_bytes(self) -> int:
         return int(lib.mlora_lora_workspace_bytes(ctypes.byref(self.c)))
 
+    def recompute_workspace_bytes(self) -> int:
+        return int(lib.mlora_lora_recompute_workspace_bytes(ctypes.byref(self.c)))
+
+    def alloc_recompute_workspace(self) -> torch.Tensor:
+        return torch.empty(self.recompute_workspace_bytes(), dtype=torch.uint8, device=self.W.device)
+
     def validate(self) -> int:
         return int(lib.mlora_lora_validate(ctypes.byref(self.c)))
 
@@ -166,6 +182,32 @@ def mlora_lora_bwd(prob: Problem, X: torch.Tensor, dY: torch.Tensor, saved: torc
                             _stream_handle(stream))
     if st != 0:
         raise MloraError(st, "mlora_lora_bwd")
+
+
+def mlora_lora_fwd_nosave(prob: Problem, X: torch.Tensor, Y: torch.Tensor, workspace: torch.Tensor,
+                          stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Forward of the activation-recompute variant: as mlora_lora_fwd, nothing saved."""
+    st = lib.mlora_lora_fwd_nosave(ctypes.byref(prob.c), X.data_ptr(), Y.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_fwd_nosave")
+
+
+def mlora_lora_bwd_recompute(prob: Problem, X: torch.Tensor, dY: torch.Tensor, dX: Optional[torch.Tensor],
+                             dA: List[torch.Tensor], dB: List[torch.Tensor], accumulate: bool,
+                             workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Backward of the activation-recompute variant: recomputes s_k x_k A_k from X."""
+    K = prob.K
+    pa = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dA])
+    pb = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dB])
+    st = lib.mlora_lora_bwd_recompute(ctypes.byref(prob.c), X.data_ptr(), dY.data_ptr(),
+                                      dX.data_ptr() if dX is not None else None,
+                                      ctypes.cast(pa, ctypes.POINTER(ctypes.c_void_p)),
+                                      ctypes.cast(pb, ctypes.POINTER(ctypes.c_void_p)), 1 if accumulate else 0,
+                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                      _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_bwd_recompute")
 
 
 def set_kernel_path(path: int) -> int:

@@ -90,6 +90,59 @@ mlora_status hip_status(hipError_t e) {
   return MLORA_ERR_HIP;
 }
 
+// Z = s_k x_k A_k into `Z` ([T, ldz], layout of the `saved` buffer)
+hipError_t compute_Z(const mlora_problem* p, const CallCtx& c, const void* X, void* Z) {
+  if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(Z))
+    return lowrank_rows_mfma(c, (const bf16*)X, c.h, (bf16*)Z, c.A, true);
+  return generic_Z(c, X, Z);
+}
+
+hipError_t forward_impl(const mlora_problem* p, const CallCtx& c, const void* X, void* Y, void* Z) {
+  hipError_t e = compute_Z(p, c, X, Z);
+  if (e != hipSuccess) return e;
+  if (mfma_gemm_applies(p) && aligned16(X) && aligned16(Y) && aligned16(Z))
+    return gemm_mfma((const bf16*)X, (const bf16*)p->W, (bf16*)Y, c.T, c.d, c.h, true, (const bf16*)Z, c.ldz, c.st, c.B,
+                     c.stream);
+  return generic_gemm_fwd(c, X, Y, Z);
+}
+
+mlora_status check_grad_tables(const mlora_problem* p, float* const* dA, float* const* dB) {
+  if (p->K > 0) {
+    if (dA == nullptr || dB == nullptr) return MLORA_ERR_NULL;
+    for (int k = 0; k < p->K; ++k)
+      if (dA[k] == nullptr || dB[k] == nullptr) return MLORA_ERR_NULL;
+  }
+  return MLORA_OK;
+}
+
+// G, dB_k, dA_k and (unless dX is NULL) dX, given Z
+hipError_t backward_impl(const mlora_problem* p, const CallCtx& c, const void* X, const void* dY, const void* Z, void* G,
+                         void* dX, float* const* dA, float* const* dB, int accumulate) {
+  OutTable ta, tb;
+  for (int k = 0; k < kMaxK; ++k) {
+    ta.p[k] = k < p->K ? dA[k] : nullptr;
+    tb.p[k] = k < p->K ? dB[k] : nullptr;
+  }
+  hipError_t e;
+  if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(dY) && aligned16(Z) && aligned16(G)) {
+    e = lowrank_rows_mfma(c, (const bf16*)dY, c.d, (bf16*)G, c.B, false);
+    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)dY, c.d, (const bf16*)Z, tb, accumulate ? 1 : 0, false);
+    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)X, c.h, (const bf16*)G, ta, accumulate ? 1 : 0, true);
+  } else {
+    e = generic_G(c, dY, G);
+    if (e == hipSuccess) e = generic_dB(c, Z, dY, tb, accumulate ? 1 : 0);
+    if (e == hipSuccess) e = generic_dA(c, X, G, ta, accumulate ? 1 : 0);
+  }
+  if (e == hipSuccess && dX != nullptr && p->T > 0) {
+    if (mfma_gemm_applies(p) && aligned16(dY) && aligned16(dX) && aligned16(G))
+      e = gemm_mfma((const bf16*)dY, (const bf16*)p->W, (bf16*)dX, c.T, c.h, c.d, false, (const bf16*)G, c.ldz, c.st, c.A,
+                    c.stream);
+    else
+      e = generic_gemm_bwd(c, dY, dX, G);
+  }
+  return e;
+}
+
 }  // namespace
 }  // namespace mlora
 
@@ -111,6 +164,12 @@ size_t mlora_lora_workspace_bytes(const mlora_problem* p) {
   return b ? b : 256;
 }
 
+size_t mlora_lora_recompute_workspace_bytes(const mlora_problem* p) {
+  if (validate(p) != MLORA_OK) return 0;
+  size_t b = 2 * lowrank_bytes(p);  // G, then Z
+  return b ? b : 256;
+}
+
 mlora_status mlora_lora_fwd(const mlora_problem* p, const void* X, void* Y, void* saved, void* workspace,
                             size_t workspace_bytes, void* hip_stream) {
   mlora_status st = validate(p);
@@ -120,18 +179,20 @@ mlora_status mlora_lora_fwd(const mlora_problem* p, const void* X, void* Y, void
   if (workspace == nullptr || workspace_bytes < mlora_lora_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
   CallCtx c;
   fill_ctx(p, hip_stream, &c);
-  hipError_t e;
-  if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(saved))
-    e = lowrank_rows_mfma(c, (const bf16*)X, c.h, (bf16*)saved, c.A, true);
-  else
-    e = generic_Z(c, X, saved);
-  if (e != hipSuccess) return hip_status(e);
-  if (mfma_gemm_applies(p) && aligned16(X) && aligned16(Y) && aligned16(saved))
-    e = gemm_mfma((const bf16*)X, (const bf16*)p->W, (bf16*)Y, c.T, c.d, c.h, true, (const bf16*)saved, c.ldz, c.st,
-                  c.B, c.stream);
-  else
-    e = generic_gemm_fwd(c, X, Y, saved);
-  return hip_status(e);
+  return hip_status(forward_impl(p, c, X, Y, saved));
+}
+
+mlora_status mlora_lora_fwd_nosave(const mlora_problem* p, const void* X, void* Y, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  mlora_status st = validate(p);
+  if (st != MLORA_OK) return st;
+  if (p->T == 0) return MLORA_OK;
+  if (X == nullptr || Y == nullptr) return MLORA_ERR_NULL;
+  if (workspace == nullptr || workspace_bytes < mlora_lora_recompute_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
+  CallCtx c;
+  fill_ctx(p, hip_stream, &c);
+  void* Z = static_cast<char*>(workspace) + lowrank_bytes(p);
+  return hip_status(forward_impl(p, c, X, Y, Z));
 }
 
 mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* dY, const void* saved, void* dX,
@@ -140,39 +201,31 @@ mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* d
   mlora_status st = validate(p);
   if (st != MLORA_OK) return st;
   if (X == nullptr || dY == nullptr || saved == nullptr) return MLORA_ERR_NULL;
-  if (p->K > 0) {
-    if (dA == nullptr || dB == nullptr) return MLORA_ERR_NULL;
-    for (int k = 0; k < p->K; ++k)
-      if (dA[k] == nullptr || dB[k] == nullptr) return MLORA_ERR_NULL;
-  }
+  st = check_grad_tables(p, dA, dB);
+  if (st != MLORA_OK) return st;
   if (workspace == nullptr || workspace_bytes < mlora_lora_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
+  if (p->T == 0 && accumulate) return MLORA_OK;
   CallCtx c;
   fill_ctx(p, hip_stream, &c);
-  OutTable ta, tb;
-  for (int k = 0; k < kMaxK; ++k) {
-    ta.p[k] = k < p->K ? dA[k] : nullptr;
-    tb.p[k] = k < p->K ? dB[k] : nullptr;
-  }
+  return hip_status(backward_impl(p, c, X, dY, saved, workspace, dX, dA, dB, accumulate));
+}
+
+mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, const void* dY, void* dX,
+                                      float* const* dA, float* const* dB, int accumulate, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  mlora_status st = validate(p);
+  if (st != MLORA_OK) return st;
+  if (X == nullptr || dY == nullptr) return MLORA_ERR_NULL;
+  st = check_grad_tables(p, dA, dB);
+  if (st != MLORA_OK) return st;
+  if (workspace == nullptr || workspace_bytes < mlora_lora_recompute_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
   if (p->T == 0 && accumulate) return MLORA_OK;
-  void* G = workspace;
-  hipError_t e;
-  if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(dY) && aligned16(saved) && aligned16(G)) {
-    e = lowrank_rows_mfma(c, (const bf16*)dY, c.d, (bf16*)G, c.B, false);
-    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)dY, c.d, (const bf16*)saved, tb, accumulate ? 1 : 0, false);
-    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)X, c.h, (const bf16*)G, ta, accumulate ? 1 : 0, true);
-  } else {
-    e = generic_G(c, dY, G);
-    if (e == hipSuccess) e = generic_dB(c, saved, dY, tb, accumulate ? 1 : 0);
-    if (e == hipSuccess) e = generic_dA(c, X, G, ta, accumulate ? 1 : 0);
-  }
-  if (e == hipSuccess && dX != nullptr && p->T > 0) {
-    if (mfma_gemm_applies(p) && aligned16(dY) && aligned16(dX) && aligned16(G))
-      e = gemm_mfma((const bf16*)dY, (const bf16*)p->W, (bf16*)dX, c.T, c.h, c.d, false, (const bf16*)G, c.ldz, c.st,
-                    c.A, c.stream);
-    else
-      e = generic_gemm_bwd(c, dY, dX, G);
-  }
-  return hip_status(e);
+  CallCtx c;
+  fill_ctx(p, hip_stream, &c);
+  void* Z = static_cast<char*>(workspace) + lowrank_bytes(p);
+  hipError_t e = p->T > 0 ? compute_Z(p, c, X, Z) : hipSuccess;
+  if (e != hipSuccess) return hip_status(e);
+  return hip_status(backward_impl(p, c, X, dY, Z, workspace, dX, dA, dB, accumulate));
 }
 
 const char* mlora_status_string(mlora_status s) {

@@ -18,15 +18,16 @@ def relerr(got: np.ndarray, ref: np.ndarray, zero_scale: float = 1.0) -> float:
     return e / n if n > 0 else e / zero_scale
 
 
-def run_hip(inp, accumulate=False, want_dx=True, preset_grads=None, poison=True):
-    """Forward + backward through the binding.  Returns dict of device tensors."""
+def run_hip(inp, accumulate=False, want_dx=True, preset_grads=None, poison=True, recompute=False):
+    """Forward + backward through the binding (the activation-recompute pair of entry points if
+    `recompute`).  Returns dict of device tensors."""
     from paper_2312_02515_amd import binding as mb
     dev = inp.X.device
     T, h = inp.X.shape
     d = inp.W.shape[1]
     prob = mb.Problem(T, h, d, inp.W, inp.seg_offsets, inp.ranks, inp.scalings, inp.A, inp.B)
     saved = prob.alloc_saved()
-    ws = prob.alloc_workspace()
+    ws = prob.alloc_recompute_workspace() if recompute else prob.alloc_workspace()
     Y = torch.empty((T, d), dtype=inp.X.dtype, device=dev)
     dX = torch.empty((T, h), dtype=inp.X.dtype, device=dev) if want_dx else None
     dA, dB = prob.alloc_grads()
@@ -44,10 +45,16 @@ def run_hip(inp, accumulate=False, want_dx=True, preset_grads=None, poison=True)
             t.copy_(v)
         for t, v in zip(dB, preset_grads[1]):
             t.copy_(v)
-    mb.mlora_lora_fwd(prob, inp.X, Y, saved, ws)
+    if recompute:
+        mb.mlora_lora_fwd_nosave(prob, inp.X, Y, ws)
+    else:
+        mb.mlora_lora_fwd(prob, inp.X, Y, saved, ws)
     if poison:
         ws.fill_(0xFF)  # the workspace carries nothing between the two calls
-    mb.mlora_lora_bwd(prob, inp.X, inp.dY, saved, dX, dA, dB, accumulate, ws)
+    if recompute:
+        mb.mlora_lora_bwd_recompute(prob, inp.X, inp.dY, dX, dA, dB, accumulate, ws)
+    else:
+        mb.mlora_lora_bwd(prob, inp.X, inp.dY, saved, dX, dA, dB, accumulate, ws)
     torch.cuda.synchronize()
     return {"Y": Y, "dX": dX, "dA": dA, "dB": dB}
 

@@ -116,6 +116,40 @@ def test_isolation_on_gpu():
     assert not torch.equal(a["Y"][256:512], b["Y"][256:512])
 
 
+def _same_bits(a, b, K):
+    assert torch.equal(a["Y"], b["Y"]) and torch.equal(a["dX"], b["dX"])
+    for k in range(K):
+        assert torch.equal(a["dA"][k], b["dA"][k]) and torch.equal(a["dB"][k], b["dB"][k])
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("case", [
+    (300, 72, 136, [100, 0, 57, 130], [4, 8, 1, 24], 5),             # generic kernels, ragged
+    (1000, 192, 320, [100, 0, 333, 500], [8, 24, 128, 64], 7),        # MFMA kernels in bf16
+    (257, 64, 64, [], [], 0),                                         # no adapters
+])
+def test_recompute_variant(dtype, case):
+    """The activation-recompute entry points (section 4.1: runs with activation checkpointing)
+    against the oracle, and bit-identical to the pair that keeps `saved`."""
+    T, h, d, tokens, ranks, lead = case
+    inp = _inputs(T, h, d, tokens, ranks, dtype, lead=lead, seed=17, scal=[1.5 - 0.25 * i for i in range(len(ranks))])
+    out = run_hip(inp, recompute=True)
+    check_full(inp, out, TOL[dtype], label=f"recompute {case}")
+    _same_bits(out, run_hip(inp), len(ranks))
+
+
+def test_recompute_variant_accumulate_skip_dx():
+    inp = _inputs(384, 128, 192, [128, 0, 200], [8, 16, 16], torch.bfloat16, lead=16, seed=3)
+    base = run_hip(inp, recompute=True)
+    pre_a = [torch.full_like(t, 0.25) for t in base["dA"]]
+    pre_b = [torch.full_like(t, -2.0) for t in base["dB"]]
+    acc = run_hip(inp, accumulate=True, want_dx=False, preset_grads=(pre_a, pre_b), recompute=True)
+    assert acc["dX"] is None
+    for k in range(3):
+        assert relerr(np64(acc["dA"][k]), np64(base["dA"][k]) + 0.25) <= 1e-6
+        assert relerr(np64(acc["dB"][k]), np64(base["dB"][k]) - 2.0) <= 1e-6
+
+
 def test_llama2_7b_qproj_full():
     """Configuration 2, every output element against the oracle."""
     w = wl.WORKLOADS["llama2_7b_qproj"]
@@ -141,6 +175,15 @@ def _sampled_workload(name, proj, per_adapter=6, grad_adapters=None):
 def test_llama2_7b_mlp_sampled(proj):
     """Configuration 3 at full size: sampled complete rows of Y and dX, all dA_k, dB_k."""
     _sampled_workload("llama2_7b_mlp", proj)
+
+
+def test_llama2_13b_layer_recompute_sampled():
+    """Configuration 4, one projection, through the activation-recompute entry points."""
+    w = wl.WORKLOADS["llama2_13b_layer"]
+    inp = wl.make_workload_inputs(w, 3, device=DEV, seed=0)
+    out = run_hip(inp, poison=False, recompute=True)
+    rows = wl.sample_rows(inp.seg_offsets, w.T, per_adapter=4, seed=2)
+    check_sampled(inp, out, TOL[torch.bfloat16], rows, grad_adapters=[0, 7, 15], label="llama2_13b_layer/o recompute")
 
 
 @pytest.mark.parametrize("proj", [0, 4, 6])

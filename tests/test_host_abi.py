@@ -105,6 +105,26 @@ def test_entry_points_reject_before_launch(mb):
     assert f(ctypes.byref(bad.c), 0x10, 0x20, 0x30, 0x40, 1 << 20, None) == 3
 
 
+def test_recompute_entry_points_reject_before_launch(mb):
+    """The activation-recompute pair: twice the workspace, same argument checks."""
+    p = _problem(mb)
+    ws = p.recompute_workspace_bytes()
+    assert ws == 2 * p.workspace_bytes()
+    f = mb.lib.mlora_lora_fwd_nosave
+    assert f(ctypes.byref(p.c), None, 0x20, 0x40, ws, None) == 1
+    assert f(ctypes.byref(p.c), 0x10, 0x20, 0x40, p.workspace_bytes(), None) == 6
+    assert f(ctypes.byref(p.c), 0x10, 0x20, None, ws, None) == 6
+    b = mb.lib.mlora_lora_bwd_recompute
+    arr = (ctypes.c_void_p * 2)(0x50, 0x60)
+    pa = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    assert b(ctypes.byref(p.c), 0x10, None, 0x30, pa, pa, 0, 0x40, ws, None) == 1
+    assert b(ctypes.byref(p.c), 0x10, 0x11, 0x30, pa, None, 0, 0x40, ws, None) == 1
+    assert b(ctypes.byref(p.c), 0x10, 0x11, 0x30, pa, pa, 0, 0x40, ws - 1, None) == 6
+    bad = _problem(mb, off=(0, 40, 30))
+    assert b(ctypes.byref(bad.c), 0x10, 0x11, 0x30, pa, pa, 0, 0x40, 1 << 20, None) == 3
+    assert mb.lib.mlora_lora_recompute_workspace_bytes(ctypes.byref(bad.c)) == 0
+
+
 def test_empty_input_is_a_noop(mb):
     p = _problem(mb, T=0, off=(0, 0, 0))
     assert p.validate() == 0
