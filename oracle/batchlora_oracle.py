@@ -34,6 +34,13 @@ each product in the equations; the steps are taken in the order the workflow
 paragraph of section 3.3.1 gives them (base product once, split, per-adapter
 low-rank products, add back at the split positions), with no blocking or fusion.
 
+Projection groups (group_forward / group_backward): several projections fed by
+the same X; their outputs are independent, dX is the sum of their input
+gradients.  Pinned by the concatenated-weight identity (the group equals one
+projection with W = [W_0 | W_1 | ...], A_k = [A_0k | A_1k | ...] and a
+block-diagonal B_k), by a doubled copy of the hand-derived example and by finite
+differences of L = sum_p sum(dY_p * Y_p).
+
 Pins (tests/test_oracle_pins.py): a hand-derived integer worked example stored
 in tests/golden/, an element-by-element scalar brute force, the merged-weight
 closed form of Eq. 1, the B = 0 special case, batched == one-adapter-at-a-time
@@ -51,6 +58,8 @@ __all__ = [
     "forward",
     "backward",
     "adapter_gradients",
+    "group_forward",
+    "group_backward",
     "gather_rows_problem",
     "flops",
 ]
@@ -133,6 +142,36 @@ def backward(X, W, dH, seg_offsets, A, B, s):
         lo, hi = int(seg_offsets[k]), int(seg_offsets[k + 1])
         dx_k = float(s[k]) * ((dH[lo:hi] @ B[k].T) @ A[k].T)
         dX[lo:hi] += dx_k
+    return dX, dA, dB
+
+
+def group_forward(X, Ws, seg_offsets, As, Bs, ss):
+    """Several LoRA-wrapped projections applied to the same input (q, k, v of one
+    attention block, gate and up of an MLP: section 4.1 puts adapters on q, k, v
+    and o of every layer).  Projection p has its own W_p [h, d_p] and its own
+    adapters A_{p,k}, B_{p,k}, s_{p,k}; all share X and the split positions.
+    Each output is Eq. "forward" on its own: returns [(H_p, Z_p) for p].
+    """
+    assert len(Ws) == len(As) == len(Bs) == len(ss)
+    return [forward(X, Ws[p], seg_offsets, As[p], Bs[p], ss[p]) for p in range(len(Ws))]
+
+
+def group_backward(X, Ws, dHs, seg_offsets, As, Bs, ss):
+    """Backward of `group_forward`.  X feeds every projection, so by the chain
+    rule its gradient is the sum over the projections of Eq. "grad_output";
+    the adapter gradients are Eq. "grad_lora" per projection.
+
+    Returns (dX [T,h], dA[p][k], dB[p][k]).
+    """
+    assert len(Ws) == len(dHs) == len(As) == len(Bs) == len(ss)
+    X = _f64(X)
+    dX = np.zeros_like(X)
+    dA, dB = [], []
+    for p in range(len(Ws)):
+        dx_p, da_p, db_p = backward(X, Ws[p], dHs[p], seg_offsets, As[p], Bs[p], ss[p])
+        dX += dx_p
+        dA.append(da_p)
+        dB.append(db_p)
     return dX, dA, dB
 
 

@@ -273,3 +273,133 @@ def test_row_sampled_problem_matches_full():
 
 def test_flops_formula():
     assert orc.flops(128, 256, 256, [0, 64, 128], [8, 8]) == 4 * 128 * 256 * 256 + 6 * 128 * 8 * 512
+
+
+# ---------------------------------------------------------------- projection groups
+def _rand_group(rng, T, h, ds, tokens, ranks_per_p, lead=0):
+    off = [lead]
+    for t in tokens:
+        off.append(off[-1] + t)
+    X = rng.standard_normal((T, h))
+    Ws = [rng.standard_normal((h, d)) / np.sqrt(h) for d in ds]
+    dHs = [rng.standard_normal((T, d)) for d in ds]
+    As = [[rng.uniform(-1, 1, (h, r)) / np.sqrt(h) for r in ranks] for ranks in ranks_per_p]
+    Bs = [[rng.standard_normal((r, d)) * 0.3 for r in ranks] for ranks, d in zip(ranks_per_p, ds)]
+    ss = [[float(v) for v in rng.uniform(0.5, 3.0, len(ranks))] for ranks in ranks_per_p]
+    return X, Ws, dHs, off, As, Bs, ss
+
+
+def test_group_equals_concatenated_projection():
+    """Projections that share X are one projection with the weights side by side:
+    W = [W_0 | W_1 | ...], A_k = [A_0k | A_1k | ...], B_k block-diagonal (the scalings
+    folded into its blocks).  Outputs are the column blocks, dX is the same matrix."""
+    rng = np.random.default_rng(41)
+    ds, rk = [5, 3, 4], [[2, 1, 3], [1, 1, 2], [3, 2, 1]]
+    X, Ws, dHs, off, As, Bs, ss = _rand_group(rng, 17, 6, ds, [4, 0, 9], rk, lead=2)
+    outs = orc.group_forward(X, Ws, off, As, Bs, ss)
+    dX, dA, dB = orc.group_backward(X, Ws, dHs, off, As, Bs, ss)
+    K, P = 3, 3
+    Wc = np.concatenate(Ws, axis=1)
+    dHc = np.concatenate(dHs, axis=1)
+    Ac = [np.concatenate([As[p][k] for p in range(P)], axis=1) for k in range(K)]
+    Bc = []
+    for k in range(K):
+        rows = []
+        for p in range(P):
+            blocks = [ss[p][k] * Bs[p][k] if q == p else np.zeros((rk[p][k], ds[q])) for q in range(P)]
+            rows.append(np.concatenate(blocks, axis=1))
+        Bc.append(np.concatenate(rows, axis=0))
+    Hc, _ = orc.forward(X, Wc, off, Ac, Bc, [1.0] * K)
+    dXc, dAc, dBc = orc.backward(X, Wc, dHc, off, Ac, Bc, [1.0] * K)
+    c0 = np.cumsum([0] + ds)
+    for p in range(P):
+        assert _relerr(outs[p][0], Hc[:, c0[p]:c0[p + 1]]) < 1e-13
+    assert _relerr(dX, dXc) < 1e-13
+    for k in range(K):
+        r0 = np.cumsum([0] + [rk[p][k] for p in range(P)])
+        for p in range(P):
+            # dA of the concatenation holds the projections' dA side by side
+            assert _relerr(dA[p][k], dAc[k][:, r0[p]:r0[p + 1]]) < 1e-12
+            # its dB holds (x A_pk)^T dH_p on the diagonal blocks, i.e. dB_pk without the scaling
+            assert _relerr(dB[p][k], ss[p][k] * dBc[k][r0[p]:r0[p + 1], c0[p]:c0[p + 1]]) < 1e-12
+
+
+def test_group_scalar_brute_force():
+    """dX[i,c] = sum_p sum_j dH_p[i,j] (W_p[c,j] + s_pk sum_q A_pk[c,q] B_pk[q,j]), element by element."""
+    rng = np.random.default_rng(43)
+    ds, rk = [3, 2], [[2, 1], [1, 2]]
+    X, Ws, dHs, off, As, Bs, ss = _rand_group(rng, 7, 4, ds, [3, 3], rk, lead=1)
+    dX, _, _ = orc.group_backward(X, Ws, dHs, off, As, Bs, ss)
+    for i in range(7):
+        k = _adapter_of_row(i, off)
+        for c in range(4):
+            acc = 0.0
+            for p in range(2):
+                for j in range(ds[p]):
+                    w = Ws[p][c, j]
+                    if k >= 0:
+                        for q in range(rk[p][k]):
+                            w += ss[p][k] * As[p][k][c, q] * Bs[p][k][q, j]
+                    acc += dHs[p][i, j] * w
+            assert abs(dX[i, c] - acc) < 1e-12
+
+
+def test_group_of_worked_example_copies():
+    """Two copies of the hand-derived example sharing X, the second one's output gradient
+    scaled by -3: outputs repeat, adapter gradients scale, dX = (1 - 3) dX by linearity."""
+    with open(os.path.join(GOLDEN, "worked_example.json")) as f:
+        g = json.load(f)
+    A = [np.array(a, float) for a in g["A"]]
+    B = [np.array(b, float) for b in g["B"]]
+    dH = np.array(g["dH"], float)
+    outs = orc.group_forward(g["X"], [g["W"]] * 2, g["seg_offsets"], [A, A], [B, B], [g["s"], g["s"]])
+    dX, dA, dB = orc.group_backward(g["X"], [g["W"]] * 2, [dH, -3.0 * dH], g["seg_offsets"], [A, A], [B, B],
+                                    [g["s"], g["s"]])
+    for p in range(2):
+        assert np.array_equal(outs[p][0], np.array(g["H"], float))
+    assert np.array_equal(dX, -2.0 * np.array(g["dX"], float))
+    for k in range(g["K"]):
+        assert np.array_equal(dA[0][k], np.array(g["dA"][k], float))
+        assert np.array_equal(dA[1][k], -3.0 * np.array(g["dA"][k], float))
+        assert np.array_equal(dB[1][k], -3.0 * np.array(g["dB"][k], float))
+
+
+def test_group_finite_differences():
+    """Central differences of L = sum_p sum(dH_p * H_p) in X and in one adapter of each projection."""
+    rng = np.random.default_rng(47)
+    ds, rk = [4, 3], [[2, 3], [1, 2]]
+    X, Ws, dHs, off, As, Bs, ss = _rand_group(rng, 9, 5, ds, [4, 5], rk)
+    dX, dA, dB = orc.group_backward(X, Ws, dHs, off, As, Bs, ss)
+
+    def loss(Xv, Av, Bv):
+        outs = orc.group_forward(Xv, Ws, off, Av, Bv, ss)
+        return sum(float(np.sum(dHs[p] * outs[p][0])) for p in range(2))
+
+    eps = 1e-6
+    num = np.zeros_like(X)
+    for i in range(X.shape[0]):
+        for c in range(X.shape[1]):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, c] += eps
+            Xm[i, c] -= eps
+            num[i, c] = (loss(Xp, As, Bs) - loss(Xm, As, Bs)) / (2 * eps)
+    assert _relerr(num, dX) < 1e-7
+    for p, k in ((0, 1), (1, 0)):
+        numA = np.zeros_like(As[p][k])
+        for i in range(numA.shape[0]):
+            for q in range(numA.shape[1]):
+                Ap = [[a.copy() for a in row] for row in As]
+                Am = [[a.copy() for a in row] for row in As]
+                Ap[p][k][i, q] += eps
+                Am[p][k][i, q] -= eps
+                numA[i, q] = (loss(X, Ap, Bs) - loss(X, Am, Bs)) / (2 * eps)
+        assert _relerr(numA, dA[p][k]) < 1e-7
+        numB = np.zeros_like(Bs[p][k])
+        for q in range(numB.shape[0]):
+            for j in range(numB.shape[1]):
+                Bp = [[b.copy() for b in row] for row in Bs]
+                Bm = [[b.copy() for b in row] for row in Bs]
+                Bp[p][k][q, j] += eps
+                Bm[p][k][q, j] -= eps
+                numB[q, j] = (loss(X, As, Bp) - loss(X, As, Bm)) / (2 * eps)
+        assert _relerr(numB, dB[p][k]) < 1e-7
