@@ -134,6 +134,33 @@ mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, con
                                       void* dX, float* const* dA, float* const* dB, int accumulate,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- Projections that share their input -------------------------------------------------
+ * Section 4.1 puts adapters on q_proj, k_proj, v_proj and o_proj of every layer; q, k and v
+ * (and gate, up of an MLP) read the same X.  A group is P problems, 1 <= P <= MLORA_MAX_GROUP,
+ * with the same T, h, K, dtype and split positions; d, W and the adapters (ranks, scalings,
+ * A_k, B_k) are each projection's own.  The forward outputs are Eq. "forward" per projection;
+ * the backward writes ONE dX, the sum over the projections of Eq. "grad_output", accumulated
+ * in fp32 and rounded once (on the MFMA path; the generic path adds projection by projection
+ * in the storage type), and Eq. "grad_lora" per projection.
+ *   ps         HOST array of P pointers to problems
+ *   Y, saved   HOST arrays of P DEVICE pointers: Y[p] is [T, d_p]; saved[p] has
+ *              mlora_lora_saved_bytes(ps[p]) bytes
+ *   dY         HOST array of P DEVICE pointers, dY[p] is [T, d_p]
+ *   dA, dB     HOST arrays of P HOST arrays of K DEVICE pointers (as in mlora_lora_bwd)
+ *   workspace  DEVICE, at least mlora_lora_group_workspace_bytes(ps, P) bytes, 256-byte aligned
+ * Errors as for the single calls; a mismatch between the problems of a group reports
+ * MLORA_ERR_SHAPE (P, T, h, K), MLORA_ERR_DTYPE or MLORA_ERR_SEGMENTS. */
+#define MLORA_MAX_GROUP 4
+mlora_status mlora_lora_group_validate(const mlora_problem* const* ps, int P);
+size_t mlora_lora_group_workspace_bytes(const mlora_problem* const* ps, int P);
+mlora_status mlora_lora_group_fwd(const mlora_problem* const* ps, int P, const void* X, void* const* Y,
+                                  void* const* saved, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream);
+mlora_status mlora_lora_group_bwd(const mlora_problem* const* ps, int P, const void* X,
+                                  const void* const* dY, const void* const* saved, void* dX,
+                                  float* const* const* dA, float* const* const* dB, int accumulate,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Plain text for a status code; never NULL. */
 const char* mlora_status_string(mlora_status s);
 

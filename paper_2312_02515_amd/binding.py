@@ -19,13 +19,15 @@ MLORA_BF16 = 0
 MLORA_F32 = 1
 MLORA_MAX_ADAPTERS = 64
 MLORA_MAX_RANK = 128
+MLORA_MAX_GROUP = 4
 
 STATUS_NAMES = {0: "MLORA_OK", 1: "MLORA_ERR_NULL", 2: "MLORA_ERR_SHAPE", 3: "MLORA_ERR_SEGMENTS",
                 4: "MLORA_ERR_RANK", 5: "MLORA_ERR_DTYPE", 6: "MLORA_ERR_WORKSPACE", 7: "MLORA_ERR_HIP"}
 
 EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_validate", "mlora_lora_fwd",
            "mlora_lora_bwd", "mlora_lora_recompute_workspace_bytes", "mlora_lora_fwd_nosave",
-           "mlora_lora_bwd_recompute", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_gemm",
+           "mlora_lora_bwd_recompute", "mlora_lora_group_validate", "mlora_lora_group_workspace_bytes",
+           "mlora_lora_group_fwd", "mlora_lora_group_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_gemm",
            "mlora_profile_gemm_read"]
 
 
@@ -76,6 +78,19 @@ def _load() -> ctypes.CDLL:
     l.mlora_lora_bwd_recompute.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
                                            ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    ppp = ctypes.POINTER(pp)
+    vpp = ctypes.POINTER(ctypes.c_void_p)
+    l.mlora_lora_group_validate.restype = ctypes.c_int
+    l.mlora_lora_group_validate.argtypes = [ppp, ctypes.c_int]
+    l.mlora_lora_group_workspace_bytes.restype = ctypes.c_size_t
+    l.mlora_lora_group_workspace_bytes.argtypes = [ppp, ctypes.c_int]
+    l.mlora_lora_group_fwd.restype = ctypes.c_int
+    l.mlora_lora_group_fwd.argtypes = [ppp, ctypes.c_int, ctypes.c_void_p, vpp, vpp, ctypes.c_void_p, ctypes.c_size_t,
+                                       ctypes.c_void_p]
+    l.mlora_lora_group_bwd.restype = ctypes.c_int
+    l.mlora_lora_group_bwd.argtypes = [ppp, ctypes.c_int, ctypes.c_void_p, vpp, vpp, ctypes.c_void_p,
+                                       ctypes.POINTER(vpp), ctypes.POINTER(vpp), ctypes.c_int, ctypes.c_void_p,
+                                       ctypes.c_size_t, ctypes.c_void_p]
     l.mlora_status_string.restype = ctypes.c_char_p
     l.mlora_status_string.argtypes = [ctypes.c_int]
     l.mlora_last_hip_error.restype = ctypes.c_int
@@ -208,6 +223,66 @@ def mlora_lora_bwd_recompute(prob: Problem, X: torch.Tensor, dY: torch.Tensor, d
                                       _stream_handle(stream))
     if st != 0:
         raise MloraError(st, "mlora_lora_bwd_recompute")
+
+
+class Group:
+    """Projections that share their input: a host array of pointers to their problems."""
+
+    def __init__(self, problems: Sequence[Problem]):
+        self.problems = list(problems)
+        self.P = len(self.problems)
+        self._arr = (ctypes.POINTER(mlora_problem) * max(self.P, 1))(*[ctypes.pointer(p.c) for p in self.problems])
+        self.c = ctypes.cast(self._arr, ctypes.POINTER(ctypes.POINTER(mlora_problem)))
+
+    def validate(self) -> int:
+        return int(lib.mlora_lora_group_validate(self.c, self.P))
+
+    def workspace_bytes(self) -> int:
+        return int(lib.mlora_lora_group_workspace_bytes(self.c, self.P))
+
+    def alloc_workspace(self) -> torch.Tensor:
+        return torch.empty(self.workspace_bytes(), dtype=torch.uint8, device=self.problems[0].W.device)
+
+
+def _ptr_array(tensors):
+    arr = (ctypes.c_void_p * max(len(tensors), 1))(*[t.data_ptr() for t in tensors])
+    return arr, ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+
+
+def mlora_lora_group_fwd(group: Group, X: torch.Tensor, Y: Sequence[torch.Tensor], saved: Sequence[torch.Tensor],
+                         workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Y[p] = X W_p + rows_k(s_pk x_k A_pk B_pk) for every projection p of the group."""
+    ky, py = _ptr_array(Y)
+    ks, ps_ = _ptr_array(saved)
+    st = lib.mlora_lora_group_fwd(group.c, group.P, X.data_ptr(), py, ps_, workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_group_fwd")
+
+
+def mlora_lora_group_bwd(group: Group, X: torch.Tensor, dY: Sequence[torch.Tensor], saved: Sequence[torch.Tensor],
+                         dX: Optional[torch.Tensor], dA: Sequence[List[torch.Tensor]],
+                         dB: Sequence[List[torch.Tensor]], accumulate: bool, workspace: torch.Tensor,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+    """One dX = sum_p (dY_p W_p^T + LoRA part); dA[p][k], dB[p][k] per projection."""
+    kd, pd = _ptr_array(dY)
+    ks, ps_ = _ptr_array(saved)
+    vpp = ctypes.POINTER(ctypes.c_void_p)
+    keep, rows_a, rows_b = [], [], []
+    for p in range(group.P):
+        a, pa = _ptr_array(dA[p])
+        b, pb = _ptr_array(dB[p])
+        keep += [a, b]
+        rows_a.append(pa)
+        rows_b.append(pb)
+    ta = (vpp * max(group.P, 1))(*rows_a)
+    tb = (vpp * max(group.P, 1))(*rows_b)
+    st = lib.mlora_lora_group_bwd(group.c, group.P, X.data_ptr(), pd, ps_, dX.data_ptr() if dX is not None else None,
+                                  ctypes.cast(ta, ctypes.POINTER(vpp)), ctypes.cast(tb, ctypes.POINTER(vpp)),
+                                  1 if accumulate else 0, workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_group_bwd")
 
 
 def set_kernel_path(path: int) -> int:

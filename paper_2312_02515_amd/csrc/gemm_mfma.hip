@@ -60,41 +60,101 @@ hipError_t gemm_profile_read(double* ms_total, double* flops_total, int* launche
 
 bool gemm_mfma_ok(int M, int N, int Kd) { return M >= 1 && (N % 64) == 0 && (Kd % 64) == 0 && N >= 64 && Kd >= 64; }
 
-// C[M,N] = A[M,Kd] * (nn ? Bm[Kd,N] : Bm[N,Kd]^T) + rows_k( L[rows_k, :r_k] * (nn ? R_k[r_k,N] : R_k[N,r_k]^T) )
-hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int Kd, bool nn, const bf16* L, int ldz,
-                     const SegTable& st, const PtrTable& R, hipStream_t stream) {
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  const dim3 grid(tiles_m * tiles_n);
-  int slot = -1;
-  {
-    std::lock_guard<std::mutex> lk(g_prof_mu);
-    if (g_prof.on && g_prof.used < kMaxProfiled) {
-      if (g_prof.used == g_prof.start.size()) {
-        hipEvent_t a, b;
-        if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
-          g_prof.start.push_back(a);
-          g_prof.stop.push_back(b);
-          g_prof.flops.push_back(0.0);
-        }
-      }
-      if (g_prof.used < g_prof.start.size()) {
-        slot = (int)g_prof.used++;
-        double f = 2.0 * M * (double)N * Kd;
-        for (int k = 0; k < st.K; ++k) f += 2.0 * (st.off[k + 1] - st.off[k]) * (double)st.rank[k] * N;
-        g_prof.flops[slot] = f;
-        (void)hipEventRecord(g_prof.start[slot], stream);
-      }
+namespace {
+
+// records the start event of a profiled launch; returns its slot or -1
+int profile_begin(double flops, hipStream_t stream) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (!g_prof.on || g_prof.used >= kMaxProfiled) return -1;
+  if (g_prof.used == g_prof.start.size()) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
+      g_prof.start.push_back(a);
+      g_prof.stop.push_back(b);
+      g_prof.flops.push_back(0.0);
     }
   }
-  if (nn)
-    hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, true, 64>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
-                       tiles_m, tiles_n);
-  else
-    hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, false, 64>), grid, dim3(512), 0, stream, A, Bm, C, M, N, Kd, L, ldz, st, R,
-                       tiles_m, tiles_n);
+  if (g_prof.used >= g_prof.start.size()) return -1;
+  const int slot = (int)g_prof.used++;
+  g_prof.flops[slot] = flops;
+  (void)hipEventRecord(g_prof.start[slot], stream);
+  return slot;
+}
+
+template <int NSEG>
+double algorithmic_flops(const gemmk::GemmArgs<NSEG>& a) {
+  double f = 0;
+  for (int g = 0; g < NSEG; ++g) {
+    f += 2.0 * a.M * (double)a.N * a.Kd[g];
+    for (int k = 0; k < a.K; ++k) f += 2.0 * (a.off[k + 1] - a.off[k]) * (double)a.rank[g][k] * a.N;
+  }
+  return f;
+}
+
+template <bool NN, int NSEG>
+hipError_t launch(const gemmk::GemmArgs<NSEG>& a, hipStream_t stream) {
+  const dim3 grid(a.tiles_m * a.tiles_n);
+  const int slot = profile_begin(algorithmic_flops(a), stream);
+  hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, NN, 64, NSEG>), grid, dim3(512), 0, stream, a);
   const hipError_t err = hipGetLastError();
   if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], stream);
   return err;
+}
+
+template <int NSEG>
+void fill_common(gemmk::GemmArgs<NSEG>* a, bf16* C, int M, int N, const SegTable& st) {
+  a->C = C;
+  a->M = M;
+  a->N = N;
+  a->tiles_m = (M + BM - 1) / BM;
+  a->tiles_n = (N + BN - 1) / BN;
+  a->K = st.K;
+  for (int k = 0; k <= kMaxK; ++k) a->off[k] = st.off[k];
+}
+
+template <int NSEG>
+hipError_t launch_sum(const GemmOperands* ops, bf16* C, int M, int N, const SegTable& st, hipStream_t stream) {
+  gemmk::GemmArgs<NSEG> a;
+  fill_common(&a, C, M, N, st);
+  for (int g = 0; g < NSEG; ++g) {
+    a.A[g] = ops[g].A;
+    a.Bm[g] = ops[g].Bm;
+    a.L[g] = ops[g].L;
+    a.Kd[g] = ops[g].Kd;
+    a.ldz[g] = ops[g].ldz;
+    for (int k = 0; k < kMaxK; ++k) a.rank[g][k] = (unsigned char)(k < st.K ? ops[g].rank[k] : 0);
+    a.R[g] = *ops[g].R;
+  }
+  return launch<false, NSEG>(a, stream);
+}
+
+}  // namespace
+
+// C[M,N] = A[M,Kd] * (nn ? Bm[Kd,N] : Bm[N,Kd]^T) + rows_k( L[rows_k, :r_k] * (nn ? R_k[r_k,N] : R_k[N,r_k]^T) )
+hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int Kd, bool nn, const bf16* L, int ldz,
+                     const SegTable& st, const PtrTable& R, hipStream_t stream) {
+  gemmk::GemmArgs<1> a;
+  fill_common(&a, C, M, N, st);
+  a.A[0] = A;
+  a.Bm[0] = Bm;
+  a.L[0] = L;
+  a.Kd[0] = Kd;
+  a.ldz[0] = ldz;
+  for (int k = 0; k < kMaxK; ++k) a.rank[0][k] = (unsigned char)(k < st.K ? st.rank[k] : 0);
+  a.R[0] = R;
+  return nn ? launch<true, 1>(a, stream) : launch<false, 1>(a, stream);
+}
+
+// C[M,N] = sum_g ( A_g[M,Kd_g] * Bm_g[N,Kd_g]^T + rows_k( L_g[rows_k, :r_gk] * R_gk[N,r_gk]^T ) ), 1 <= n <= 4
+hipError_t gemm_mfma_sum_nt(int n, const GemmOperands* ops, bf16* C, int M, int N, const SegTable& st,
+                            hipStream_t stream) {
+  switch (n) {
+    case 1: return launch_sum<1>(ops, C, M, N, st, stream);
+    case 2: return launch_sum<2>(ops, C, M, N, st, stream);
+    case 3: return launch_sum<3>(ops, C, M, N, st, stream);
+    case 4: return launch_sum<4>(ops, C, M, N, st, stream);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace mlora

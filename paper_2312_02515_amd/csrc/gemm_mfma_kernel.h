@@ -29,6 +29,26 @@ using namespace stage;
 
 constexpr int BM = 256, BN = 256;
 
+// Kernel arguments (passed by value, read with scalar loads).  The contraction may run over
+// NSEG operand pairs in turn, all accumulating into the same output tile:
+//   C = sum_g ( A_g[M,Kd_g] * op(Bm_g) + rows_k( L_g[rows_k, :r_gk] * R_gk ) )
+// NSEG = 1 is the plain operator; NSEG > 1 is the input gradient of several projections that
+// share their input (dX = sum_p dY_p W_p^T + ...), kept in fp32 until the single store.
+template <int NSEG>
+struct GemmArgs {
+  bf16* C;
+  int M, N, tiles_m, tiles_n;
+  int K;                                 // tasks
+  int off[kMaxK + 1];                    // split positions (rows of C)
+  const bf16* A[NSEG];                   // [M, Kd_g]
+  const bf16* Bm[NSEG];                  // NN: [Kd_g, N]; NT: [N, Kd_g]
+  const bf16* L[NSEG];                   // [M, ldz_g] low-rank intermediate (Z or G)
+  int Kd[NSEG];
+  int ldz[NSEG];
+  unsigned char rank[NSEG][kMaxK];       // r_gk <= 128
+  PtrTable R[NSEG];                      // NN: B_k [r, N]; NT: A_k [N, r]
+};
+
 // ------------------------------------------------------------------------------------------
 // Schedule.  Contraction tiles of 64 (rows of 128 B, so every request to the L2 is a full cache
 // line), double-buffered in LDS; tile kt+1 is fetched while tile kt is computed.  Every memory
@@ -47,11 +67,11 @@ constexpr int BM = 256, BN = 256;
 // Contraction tiles of 32 in a 4- or 5-stage ring (deeper prefetch, half-line requests) were
 // measured 7 % slower on the K-contiguous operands and equal on the forward's W tile.
 // ------------------------------------------------------------------------------------------
-template <int WAVES_M, int WAVES_N, bool NN, int BK>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
-    const bf16* __restrict__ A, const bf16* __restrict__ Bm, bf16* __restrict__ C, int M, int N, int Kd,
-    const bf16* __restrict__ L, int ldz, SegTable st, PtrTable R, int tiles_m, int tiles_n) {
+template <int WAVES_M, int WAVES_N, bool NN, int BK, int NSEG>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmArgs<NSEG> ga) {
   static_assert(BK == 64, "contraction tile");
+  bf16* __restrict__ C = ga.C;
+  const int M = ga.M, N = ga.N, tiles_m = ga.tiles_m, tiles_n = ga.tiles_n;
   constexpr int NS = 2;                        // LDS stages: 2 x (32 + 32) KiB
   constexpr int KS = BK / 16;                  // MFMA steps per contraction tile
   constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
@@ -100,35 +120,41 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
   }
 
   // ---- direct-to-LDS loads: wave-uniform base of the tile's rows (advanced per contraction
-  // tile with scalar arithmetic) plus a constant 32-bit per-lane byte offset
-  const char* abase = reinterpret_cast<const char*>(A + (size_t)row0 * Kd);
-  const char* bbase = NN ? reinterpret_cast<const char*>(Bm + col0) : reinterpret_cast<const char*>(Bm + (size_t)col0 * Kd);
+  // tile with scalar arithmetic) plus a constant 32-bit per-lane byte offset; both are set per
+  // operand pair by set_operands()
+  const char* abase = nullptr;
+  const char* bbase = nullptr;
   unsigned aoff[LPW], boff[LPW];
+  size_t bstep = 0;  // bytes per contraction tile of Bm
+  auto set_operands = [&](const bf16* A, const bf16* Bm, int Kd) {
+    abase = reinterpret_cast<const char*>(A + (size_t)row0 * Kd);
+    bbase = NN ? reinterpret_cast<const char*>(Bm + col0) : reinterpret_cast<const char*>(Bm + (size_t)col0 * Kd);
 #pragma unroll
-  for (int it = 0; it < LPW; ++it) {
-    const int w = wave + NW * it;
-    {
-      const int rl = RPI * w + lane / CPR;
-      const int c = (lane % CPR) ^ ((rl / RW) % CPR);
-      int gr = row0 + rl;
-      gr = gr < M ? gr : M - 1;
-      aoff[it] = (unsigned)(((size_t)(gr - row0) * Kd + c * 8) * 2);
+    for (int it = 0; it < LPW; ++it) {
+      const int w = wave + NW * it;
+      {
+        const int rl = RPI * w + lane / CPR;
+        const int c = (lane % CPR) ^ ((rl / RW) % CPR);
+        int gr = row0 + rl;
+        gr = gr < M ? gr : M - 1;
+        aoff[it] = (unsigned)(((size_t)(gr - row0) * Kd + c * 8) * 2);
+      }
+      if (NN) {
+        const int kr = 2 * w + (lane >> 5);
+        const int c = (lane & 31) ^ ((kr & 3) << 2);
+        int n = col0 + c * 8;
+        n = n < N ? n : N - 8;
+        boff[it] = (unsigned)(((size_t)kr * N + (n - col0)) * 2);
+      } else {
+        const int rl = RPI * w + lane / CPR;
+        const int c = (lane % CPR) ^ ((rl / RW) % CPR);
+        int gn = col0 + rl;
+        gn = gn < N ? gn : N - 1;
+        boff[it] = (unsigned)(((size_t)(gn - col0) * Kd + c * 8) * 2);
+      }
     }
-    if (NN) {
-      const int kr = 2 * w + (lane >> 5);
-      const int c = (lane & 31) ^ ((kr & 3) << 2);
-      int n = col0 + c * 8;
-      n = n < N ? n : N - 8;
-      boff[it] = (unsigned)(((size_t)kr * N + (n - col0)) * 2);
-    } else {
-      const int rl = RPI * w + lane / CPR;
-      const int c = (lane % CPR) ^ ((rl / RW) % CPR);
-      int gn = col0 + rl;
-      gn = gn < N ? gn : N - 1;
-      boff[it] = (unsigned)(((size_t)(gn - col0) * Kd + c * 8) * 2);
-    }
-  }
-  const size_t bstep = (NN ? (size_t)BK * N : (size_t)BK) * 2;  // bytes per contraction tile
+    bstep = (NN ? (size_t)BK * N : (size_t)BK) * 2;
+  };
 
   // the idx-th of the PER_TILE wave-wide loads of contraction tile kt
   auto issue_one = [&](int kt, int idx, char* sa, char* sb) {
@@ -195,36 +221,42 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
 
   // ---- main contraction loop (unrolled by the two stages so that stage addresses are constants)
   static_assert(NS == 2 && KS == 4, "loop below is written for a double buffer of 4-step tiles");
-  const int KT = Kd / BK;
+  // Operand pairs run one after the other.  When a pair's last tile has passed its barrier every
+  // wave holds that tile's last fragments in registers, so both stages are free for the next
+  // pair's first two tiles.
+  for (int sg = 0; sg < NSEG; ++sg) {
+    set_operands(ga.A[sg], ga.Bm[sg], ga.Kd[sg]);
+    const int KT = ga.Kd[sg] / BK;
 #pragma unroll
-  for (int idx = 0; idx < PER_TILE; ++idx) issue_one(0, idx, sA[0], sB[0]);
-  if (KT > 1) {
+    for (int idx = 0; idx < PER_TILE; ++idx) issue_one(0, idx, sA[0], sB[0]);
+    if (KT > 1) {
 #pragma unroll
-    for (int idx = 0; idx < PER_TILE; ++idx) issue_one(1, idx, sA[1], sB[1]);
-    wait_vmcnt<PER_TILE>();
-  } else {
-    wait_vmcnt<0>();
-  }
-  __builtin_amdgcn_s_barrier();
+      for (int idx = 0; idx < PER_TILE; ++idx) issue_one(1, idx, sA[1], sB[1]);
+      wait_vmcnt<PER_TILE>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
-  __builtin_amdgcn_sched_barrier(0);
-  for (int kt0 = 0; kt0 < KT; kt0 += 2) {
+    for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int kt0 = 0; kt0 < KT; kt0 += 2) {
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int kt = kt0 + s;
-      if (kt < KT) {
-        step(0, true, sA[s], sB[s], 1, false, 0, nullptr, nullptr);
-        step(1, true, sA[s], sB[s], 2, false, 0, nullptr, nullptr);
-        step(0, true, sA[s], sB[s], 3, false, 0, nullptr, nullptr);
-        // tile kt+1 has landed (this wave's part), every fragment of tile kt is in registers
-        wait_vmcnt<0>();
-        wait_lds();
-        __builtin_amdgcn_s_barrier();
-        step(1, kt + 1 < KT, sA[s ^ 1], sB[s ^ 1], 0, kt + 2 < KT, kt + 2, sA[s], sB[s]);
+      for (int s = 0; s < 2; ++s) {
+        const int kt = kt0 + s;
+        if (kt < KT) {
+          step(0, true, sA[s], sB[s], 1, false, 0, nullptr, nullptr);
+          step(1, true, sA[s], sB[s], 2, false, 0, nullptr, nullptr);
+          step(0, true, sA[s], sB[s], 3, false, 0, nullptr, nullptr);
+          // tile kt+1 has landed (this wave's part), every fragment of tile kt is in registers
+          wait_vmcnt<0>();
+          wait_lds();
+          __builtin_amdgcn_s_barrier();
+          step(1, kt + 1 < KT, sA[s ^ 1], sB[s ^ 1], 0, kt + 2 < KT, kt + 2, sA[s], sB[s]);
+        }
       }
     }
-  }
+  }  // operand pairs
 
   // ---- LoRA extension steps (the stages are free now: every load has landed and every wave
   // passed the last barrier after its last fragment read)
@@ -243,38 +275,42 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(
     }
   };
   const int rend = (row0 + BM) < M ? (row0 + BM) : M;
-  for (int k = 0; k < st.K; ++k) {
-    const int lo = st.off[k] > row0 ? st.off[k] : row0;
-    const int hi = st.off[k + 1] < rend ? st.off[k + 1] : rend;
-    if (lo >= hi) continue;
-    const int r = st.rank[k];
-    const bf16* Rk = static_cast<const bf16*>(R.p[k]);
-    for (int q0 = 0; q0 < r; q0 += BK) {
-      __syncthreads();
-      for (int e = tid; e < BM * CPR; e += NT) {
-        const int rl = e / CPR, c = e % CPR;
-        const int row = row0 + rl, q = q0 + c * 8;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (row >= lo && row < hi && q < ldz) v = *(const uint4*)(L + (size_t)row * ldz + q);
-        *(uint4*)(sA0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
-      }
-      for (int e = tid; e < BM * CPR; e += NT) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (NN) {
-          const int kr = e >> 5, c = e & 31;
-          const int q = q0 + kr, n = col0 + c * 8;
-          if (q < r && n < N) v = *(const uint4*)(Rk + (size_t)q * N + n);
-          *(uint4*)(sB0 + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = v;
-        } else {
+  for (int sg = 0; sg < NSEG; ++sg) {
+    const bf16* __restrict__ L = ga.L[sg];
+    const int ldz = ga.ldz[sg];
+    for (int k = 0; k < ga.K; ++k) {
+      const int lo = ga.off[k] > row0 ? ga.off[k] : row0;
+      const int hi = ga.off[k + 1] < rend ? ga.off[k + 1] : rend;
+      if (lo >= hi) continue;
+      const int r = ga.rank[sg][k];
+      const bf16* Rk = static_cast<const bf16*>(ga.R[sg].p[k]);
+      for (int q0 = 0; q0 < r; q0 += BK) {
+        __syncthreads();
+        for (int e = tid; e < BM * CPR; e += NT) {
           const int rl = e / CPR, c = e % CPR;
-          const int n = col0 + rl, q = q0 + c * 8;
-          if (n < N && q < r) v = *(const uint4*)(Rk + (size_t)n * r + q);
-          *(uint4*)(sB0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
+          const int row = row0 + rl, q = q0 + c * 8;
+          uint4 v = make_uint4(0, 0, 0, 0);
+          if (row >= lo && row < hi && q < ldz) v = *(const uint4*)(L + (size_t)row * ldz + q);
+          *(uint4*)(sA0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
         }
+        for (int e = tid; e < BM * CPR; e += NT) {
+          uint4 v = make_uint4(0, 0, 0, 0);
+          if (NN) {
+            const int kr = e >> 5, c = e & 31;
+            const int q = q0 + kr, n = col0 + c * 8;
+            if (q < r && n < N) v = *(const uint4*)(Rk + (size_t)q * N + n);
+            *(uint4*)(sB0 + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = v;
+          } else {
+            const int rl = e / CPR, c = e % CPR;
+            const int n = col0 + rl, q = q0 + c * 8;
+            if (n < N && q < r) v = *(const uint4*)(Rk + (size_t)n * r + q);
+            *(uint4*)(sB0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
+          }
+        }
+        __syncthreads();
+        const int left = (r - q0 + 15) / 16;
+        ext_compute(left < KS ? left : KS);
       }
-      __syncthreads();
-      const int left = (r - q0 + 15) / 16;
-      ext_compute(left < KS ? left : KS);
     }
   }
 

@@ -41,12 +41,12 @@ __global__ void k_lowrank_rows(const T* __restrict__ In, int rows, int inner, T*
   }
 }
 
-// C[M,N] = A[M,Kd] * op(Bm) + L[M,:r_k] * R_k   (64x64 tile, 16x16 threads, 4x4 each)
+// C[M,N] (+)= A[M,Kd] * op(Bm) + L[M,:r_k] * R_k   (64x64 tile, 16x16 threads, 4x4 each)
 //   TRANSB = false: Bm is [Kd, N] row-major;  R_k(q, j) = Rk[q * N + j]   (forward:  W, B_k)
 //   TRANSB = true : Bm is [N, Kd] row-major;  R_k(q, j) = Rk[j * r + q]   (backward: W, A_k)
 template <typename T, bool TRANSB>
 __global__ void k_gemm_lora(const T* __restrict__ A, const T* __restrict__ Bm, T* __restrict__ C, int M, int N,
-                            int Kd, const T* __restrict__ L, int ldz, SegTable st, PtrTable R) {
+                            int Kd, const T* __restrict__ L, int ldz, SegTable st, PtrTable R, int accumulate) {
   constexpr int TS = 64, BK = 16;
   __shared__ float As[BK][TS + 1];
   __shared__ float Bs[BK][TS + 1];
@@ -101,7 +101,8 @@ __global__ void k_gemm_lora(const T* __restrict__ A, const T* __restrict__ Bm, T
         float rv = TRANSB ? to_f32(Rk[(size_t)gc * r + q]) : to_f32(Rk[(size_t)q * N + gc]);
         lo += to_f32(L[(size_t)gr * ldz + q]) * rv;
       }
-      C[(size_t)gr * N + gc] = from_f32<T>(acc[u][v] + lo);
+      T* dst = C + (size_t)gr * N + gc;
+      *dst = from_f32<T>(acc[u][v] + lo + (accumulate ? to_f32(*dst) : 0.f));
     }
   }
 }
@@ -141,11 +142,11 @@ hipError_t lowrank_t(const CallCtx& c, const T* In, int inner, T* Out, const Ptr
 }
 
 template <typename T, bool TRANSB>
-hipError_t gemm_t(const CallCtx& c, const T* A, T* C, int N, int Kd, const T* L, const PtrTable& R) {
+hipError_t gemm_t(const CallCtx& c, const T* A, T* C, int N, int Kd, const T* L, const PtrTable& R, int accumulate = 0) {
   if (c.T > 0) {
     dim3 grid((c.T + 63) / 64, (N + 63) / 64);
     hipLaunchKernelGGL((k_gemm_lora<T, TRANSB>), grid, dim3(256), 0, c.stream, A, static_cast<const T*>(c.W), C, c.T,
-                       N, Kd, L, c.ldz, c.st, R);
+                       N, Kd, L, c.ldz, c.st, R, accumulate);
   }
   return hipGetLastError();
 }
@@ -175,9 +176,9 @@ hipError_t generic_gemm_fwd(const CallCtx& c, const void* X, void* Y, const void
                   (gemm_t<bf16, false>(c, (const bf16*)X, (bf16*)Y, c.d, c.h, (const bf16*)Z, c.B)));
 }
 
-hipError_t generic_gemm_bwd(const CallCtx& c, const void* dY, void* dX, const void* G) {
-  return DISPATCH((gemm_t<float, true>(c, (const float*)dY, (float*)dX, c.h, c.d, (const float*)G, c.A)),
-                  (gemm_t<bf16, true>(c, (const bf16*)dY, (bf16*)dX, c.h, c.d, (const bf16*)G, c.A)));
+hipError_t generic_gemm_bwd(const CallCtx& c, const void* dY, void* dX, const void* G, int accumulate) {
+  return DISPATCH((gemm_t<float, true>(c, (const float*)dY, (float*)dX, c.h, c.d, (const float*)G, c.A, accumulate)),
+                  (gemm_t<bf16, true>(c, (const bf16*)dY, (bf16*)dX, c.h, c.d, (const bf16*)G, c.A, accumulate)));
 }
 
 hipError_t generic_dB(const CallCtx& c, const void* Z, const void* dY, const OutTable& dB, int accumulate) {

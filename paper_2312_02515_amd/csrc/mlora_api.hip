@@ -115,9 +115,9 @@ mlora_status check_grad_tables(const mlora_problem* p, float* const* dA, float* 
   return MLORA_OK;
 }
 
-// G, dB_k, dA_k and (unless dX is NULL) dX, given Z
-hipError_t backward_impl(const mlora_problem* p, const CallCtx& c, const void* X, const void* dY, const void* Z, void* G,
-                         void* dX, float* const* dA, float* const* dB, int accumulate) {
+// G, dB_k and dA_k, given Z
+hipError_t adapter_grads_impl(const mlora_problem* p, const CallCtx& c, const void* X, const void* dY, const void* Z,
+                              void* G, float* const* dA, float* const* dB, int accumulate) {
   OutTable ta, tb;
   for (int k = 0; k < kMaxK; ++k) {
     ta.p[k] = k < p->K ? dA[k] : nullptr;
@@ -133,6 +133,13 @@ hipError_t backward_impl(const mlora_problem* p, const CallCtx& c, const void* X
     if (e == hipSuccess) e = generic_dB(c, Z, dY, tb, accumulate ? 1 : 0);
     if (e == hipSuccess) e = generic_dA(c, X, G, ta, accumulate ? 1 : 0);
   }
+  return e;
+}
+
+// G, dB_k, dA_k and (unless dX is NULL) dX, given Z
+hipError_t backward_impl(const mlora_problem* p, const CallCtx& c, const void* X, const void* dY, const void* Z, void* G,
+                         void* dX, float* const* dA, float* const* dB, int accumulate) {
+  hipError_t e = adapter_grads_impl(p, c, X, dY, Z, G, dA, dB, accumulate);
   if (e == hipSuccess && dX != nullptr && p->T > 0) {
     if (mfma_gemm_applies(p) && aligned16(dY) && aligned16(dX) && aligned16(G))
       e = gemm_mfma((const bf16*)dY, (const bf16*)p->W, (bf16*)dX, c.T, c.h, c.d, false, (const bf16*)G, c.ldz, c.st, c.A,
@@ -141,6 +148,23 @@ hipError_t backward_impl(const mlora_problem* p, const CallCtx& c, const void* X
       e = generic_gemm_bwd(c, dY, dX, G);
   }
   return e;
+}
+
+// A group is valid when each member is and all share T, h, K, the dtype and the split positions.
+mlora_status validate_group(const mlora_problem* const* ps, int P) {
+  if (ps == nullptr) return MLORA_ERR_NULL;
+  if (P < 1 || P > MLORA_MAX_GROUP) return MLORA_ERR_SHAPE;
+  for (int p = 0; p < P; ++p) {
+    mlora_status st = validate(ps[p]);
+    if (st != MLORA_OK) return st;
+  }
+  for (int p = 1; p < P; ++p) {
+    if (ps[p]->dtype != ps[0]->dtype) return MLORA_ERR_DTYPE;
+    if (ps[p]->T != ps[0]->T || ps[p]->h != ps[0]->h || ps[p]->K != ps[0]->K) return MLORA_ERR_SHAPE;
+    for (int k = 0; k <= ps[0]->K && ps[0]->K > 0; ++k)
+      if (ps[p]->seg_offsets[k] != ps[0]->seg_offsets[k]) return MLORA_ERR_SEGMENTS;
+  }
+  return MLORA_OK;
 }
 
 }  // namespace
@@ -226,6 +250,88 @@ mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, con
   hipError_t e = p->T > 0 ? compute_Z(p, c, X, Z) : hipSuccess;
   if (e != hipSuccess) return hip_status(e);
   return hip_status(backward_impl(p, c, X, dY, Z, workspace, dX, dA, dB, accumulate));
+}
+
+mlora_status mlora_lora_group_validate(const mlora_problem* const* ps, int P) { return validate_group(ps, P); }
+
+size_t mlora_lora_group_workspace_bytes(const mlora_problem* const* ps, int P) {
+  if (validate_group(ps, P) != MLORA_OK) return 0;
+  size_t b = 0;
+  for (int p = 0; p < P; ++p) b += lowrank_bytes(ps[p]);  // every G_p is live until dX is written
+  return b ? b : 256;
+}
+
+mlora_status mlora_lora_group_fwd(const mlora_problem* const* ps, int P, const void* X, void* const* Y,
+                                  void* const* saved, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  mlora_status st = validate_group(ps, P);
+  if (st != MLORA_OK) return st;
+  if (ps[0]->T == 0) return MLORA_OK;
+  if (X == nullptr || Y == nullptr || saved == nullptr) return MLORA_ERR_NULL;
+  for (int p = 0; p < P; ++p)
+    if (Y[p] == nullptr || saved[p] == nullptr) return MLORA_ERR_NULL;
+  if (workspace == nullptr || workspace_bytes < mlora_lora_group_workspace_bytes(ps, P)) return MLORA_ERR_WORKSPACE;
+  for (int p = 0; p < P; ++p) {
+    CallCtx c;
+    fill_ctx(ps[p], hip_stream, &c);
+    hipError_t e = forward_impl(ps[p], c, X, Y[p], saved[p]);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  return MLORA_OK;
+}
+
+mlora_status mlora_lora_group_bwd(const mlora_problem* const* ps, int P, const void* X, const void* const* dY,
+                                  const void* const* saved, void* dX, float* const* const* dA,
+                                  float* const* const* dB, int accumulate, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+  mlora_status st = validate_group(ps, P);
+  if (st != MLORA_OK) return st;
+  if (X == nullptr || dY == nullptr || saved == nullptr) return MLORA_ERR_NULL;
+  for (int p = 0; p < P; ++p)
+    if (dY[p] == nullptr || saved[p] == nullptr) return MLORA_ERR_NULL;
+  if (ps[0]->K > 0) {
+    if (dA == nullptr || dB == nullptr) return MLORA_ERR_NULL;
+    for (int p = 0; p < P; ++p) {
+      st = check_grad_tables(ps[p], dA[p], dB[p]);
+      if (st != MLORA_OK) return st;
+    }
+  }
+  if (workspace == nullptr || workspace_bytes < mlora_lora_group_workspace_bytes(ps, P)) return MLORA_ERR_WORKSPACE;
+  if (ps[0]->T == 0 && accumulate) return MLORA_OK;
+
+  CallCtx c[MLORA_MAX_GROUP];
+  void* G[MLORA_MAX_GROUP];
+  char* w = static_cast<char*>(workspace);
+  bool sum_kernel = dX != nullptr && aligned16(dX);
+  for (int p = 0; p < P; ++p) {
+    fill_ctx(ps[p], hip_stream, &c[p]);
+    G[p] = w;
+    w += lowrank_bytes(ps[p]);
+    sum_kernel = sum_kernel && mfma_gemm_applies(ps[p]) && aligned16(dY[p]) && aligned16(G[p]);
+  }
+  for (int p = 0; p < P; ++p) {
+    hipError_t e = adapter_grads_impl(ps[p], c[p], X, dY[p], saved[p], G[p], ps[0]->K > 0 ? dA[p] : nullptr,
+                                      ps[0]->K > 0 ? dB[p] : nullptr, accumulate);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  if (dX == nullptr || ps[0]->T == 0) return MLORA_OK;
+  hipError_t e = hipSuccess;
+  if (sum_kernel) {
+    // one kernel: the P products accumulate in fp32 in the same output tile, dX is written once
+    GemmOperands ops[MLORA_MAX_GROUP];
+    for (int p = 0; p < P; ++p) {
+      ops[p].A = (const bf16*)dY[p];
+      ops[p].Bm = (const bf16*)ps[p]->W;
+      ops[p].L = (const bf16*)G[p];
+      ops[p].Kd = c[p].d;
+      ops[p].ldz = c[p].ldz;
+      ops[p].rank = c[p].st.rank;
+      ops[p].R = &c[p].A;
+    }
+    e = gemm_mfma_sum_nt(P, ops, (bf16*)dX, c[0].T, c[0].h, c[0].st, c[0].stream);
+  } else {
+    for (int p = 0; p < P && e == hipSuccess; ++p) e = generic_gemm_bwd(c[p], dY[p], dX, G[p], p > 0 ? 1 : 0);
+  }
+  return hip_status(e);
 }
 
 const char* mlora_status_string(mlora_status s) {

@@ -74,7 +74,8 @@ struct CallCtx {
 hipError_t generic_Z(const CallCtx& c, const void* X, void* Z);                        // Z = s x A
 hipError_t generic_G(const CallCtx& c, const void* dY, void* G);                       // G = s dy B^T
 hipError_t generic_gemm_fwd(const CallCtx& c, const void* X, void* Y, const void* Z);  // Y = X W + Z B
-hipError_t generic_gemm_bwd(const CallCtx& c, const void* dY, void* dX, const void* G);  // dX = dY W^T + G A^T
+// dX (+)= dY W^T + G A^T; with `accumulate` the sum is added to what dX holds (in its storage type)
+hipError_t generic_gemm_bwd(const CallCtx& c, const void* dY, void* dX, const void* G, int accumulate = 0);
 hipError_t generic_dB(const CallCtx& c, const void* Z, const void* dY, const OutTable& dB, int accumulate);
 hipError_t generic_dA(const CallCtx& c, const void* X, const void* G, const OutTable& dA, int accumulate);
 
@@ -82,6 +83,19 @@ hipError_t generic_dA(const CallCtx& c, const void* X, const void* G, const OutT
 bool gemm_mfma_ok(int M, int N, int Kd);
 hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int Kd, bool nn, const bf16* L, int ldz,
                      const SegTable& st, const PtrTable& R, hipStream_t stream);
+
+// One operand pair of a summed contraction (the input gradient of projections that share X):
+// A [M, Kd], Bm [N, Kd], L [M, ldz] with R_k [N, rank[k]].
+struct GemmOperands {
+  const bf16* A;
+  const bf16* Bm;
+  const bf16* L;
+  int Kd, ldz;
+  const int* rank;     // K entries
+  const PtrTable* R;
+};
+hipError_t gemm_mfma_sum_nt(int n, const GemmOperands* ops, bf16* C, int M, int N, const SegTable& st,
+                            hipStream_t stream);
 
 int gemm_profile_enable(int enable);
 hipError_t gemm_profile_read(double* ms_total, double* flops_total, int* launches);

@@ -125,6 +125,44 @@ def test_recompute_entry_points_reject_before_launch(mb):
     assert mb.lib.mlora_lora_recompute_workspace_bytes(ctypes.byref(bad.c)) == 0
 
 
+def test_group_validation(mb):
+    """Projection groups: members must agree on T, h, K, dtype and split positions."""
+    a, b = _problem(mb), _problem(mb, d=80, ranks=(16, 8))
+    g = mb.Group([a, b])
+    assert g.validate() == 0
+    assert g.workspace_bytes() == a.workspace_bytes() + b.workspace_bytes()
+    assert mb.Group([a]).validate() == 0
+    assert mb.Group([]).validate() == 2
+    assert mb.Group([a] * (mb.MLORA_MAX_GROUP + 1)).validate() == 2
+    assert mb.Group([a, _problem(mb, h=64)]).validate() == 2
+    assert mb.Group([a, _problem(mb, T=96)]).validate() == 2
+    assert mb.Group([a, _problem(mb, off=(0, 16, 64))]).validate() == 3
+    assert mb.Group([a, _problem(mb, off=(0, 32, 64, 64), ranks=(8, 4, 4), s=(1.0, 1.0, 1.0))]).validate() == 2
+    assert mb.Group([a, _problem(mb, ranks=(8, 200))]).validate() == 4
+    c = _problem(mb)
+    c.c.dtype = mb.MLORA_F32
+    assert mb.Group([a, c]).validate() == 5
+    assert mb.Group([a, c]).workspace_bytes() == 0
+    assert mb.lib.mlora_lora_group_validate(None, 2) == 1
+    # entry points reject before any launch
+    ws = g.workspace_bytes()
+    two = (ctypes.c_void_p * 2)(0x50, 0x60)
+    p2 = ctypes.cast(two, ctypes.POINTER(ctypes.c_void_p))
+    hole = (ctypes.c_void_p * 2)(0x50, None)
+    ph = ctypes.cast(hole, ctypes.POINTER(ctypes.c_void_p))
+    f = mb.lib.mlora_lora_group_fwd
+    assert f(g.c, 2, None, p2, p2, 0x40, ws, None) == 1
+    assert f(g.c, 2, 0x10, ph, p2, 0x40, ws, None) == 1
+    assert f(g.c, 2, 0x10, p2, p2, 0x40, ws - 1, None) == 6
+    vpp = ctypes.POINTER(ctypes.c_void_p)
+    tab = (vpp * 2)(p2, p2)
+    pt = ctypes.cast(tab, ctypes.POINTER(vpp))
+    bw = mb.lib.mlora_lora_group_bwd
+    assert bw(g.c, 2, 0x10, ph, p2, 0x30, pt, pt, 0, 0x40, ws, None) == 1
+    assert bw(g.c, 2, 0x10, p2, p2, 0x30, None, pt, 0, 0x40, ws, None) == 1
+    assert bw(g.c, 2, 0x10, p2, p2, 0x30, pt, pt, 0, None, ws, None) == 6
+
+
 def test_empty_input_is_a_noop(mb):
     p = _problem(mb, T=0, off=(0, 0, 0))
     assert p.validate() == 0
