@@ -23,48 +23,82 @@ using namespace stage;
 
 
 // ------------------------------------------------------------------------------------------
-// Out[i, 0:ldz] = s_k * In[i, :] * M_k   for the rows i of task k; columns >= r_k are zero.
+// Arguments of the two kernels, passed by value.  NP > 1 serves projections that share their
+// input: the big operand (X) is streamed once and multiplied with every projection's small
+// operand; each projection has its own ranks, scalings, pointers and output.
+// ------------------------------------------------------------------------------------------
+template <int NP>
+struct RowsArgs {
+  const bf16* In;                       // [T, inner]
+  int inner;
+  int K;
+  int off[kMaxK + 1];
+  bf16* Out[NP];                        // [T, ldz_p]
+  int ldz[NP];
+  unsigned char rank[NP][kMaxK];
+  float s[NP][kMaxK];
+  PtrTable M[NP];
+};
+
+template <int NP>
+struct GradArgs {
+  const bf16* Big;                      // [T, wide]
+  int wide, T;
+  int K;
+  int off[kMaxK + 1];
+  const bf16* Small[NP];                // [T, ldz_p]
+  int ldz[NP];
+  unsigned char rank[NP][kMaxK];
+  OutTable out[NP];
+  int accumulate, chunks;
+};
+
+// ------------------------------------------------------------------------------------------
+// Out_p[i, 0:ldz_p] = s_pk * In[i, :] * M_pk   for the rows i of task k; columns >= r_pk are zero.
 //   SMALL_KMAJOR = true : M_k = A_k  [inner, r_k]  (rows of A_k are contraction indices)
 //   SMALL_KMAJOR = false: M_k = B_k^T, B_k [r_k, inner]
 // Block: TM rows of one task (TM = 32, 64 or 128), one wave per 32 rows, contraction tiles of 64.
+// NQ = 32-column groups of the widest Out_p.
 // ------------------------------------------------------------------------------------------
-template <bool SMALL_KMAJOR, int NQ, int NS, int TM>
-__global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const bf16* __restrict__ In, int inner,
-                                                         bf16* __restrict__ Out, int ldz, SegTable st, PtrTable Mp) {
+template <bool SMALL_KMAJOR, int NQ, int NS, int TM, int NP>
+__global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const RowsArgs<NP> ra) {
   constexpr int NWV = TM / 32;                     // waves per block
-  constexpr int SPW = (4 * NQ + NWV - 1) / NWV;    // 1 KiB pieces of the small operand per wave
+  constexpr int SPW = (4 * NQ + NWV - 1) / NWV;    // 1 KiB pieces of one small operand per wave
   constexpr int SBYTES = NQ * 32 * 128;
+  // a small-operand tile is followed by 64 zero bytes: where lanes beyond the tile's columns point
+  constexpr int SREG = SBYTES + 1024;              // per projection; keeps every 1 KiB load slot aligned
   __shared__ __attribute__((aligned(1024))) char sX0[TM * 128];
   __shared__ __attribute__((aligned(1024))) char sX1[TM * 128];
   __shared__ __attribute__((aligned(1024))) char sX2[TM * 128];
   __shared__ __attribute__((aligned(1024))) char sX3[NS > 3 ? TM * 128 : 16];
-  // 64 zero bytes behind each small-operand tile: where lanes beyond the tile's columns point
-  __shared__ __attribute__((aligned(1024))) char sS0[SBYTES + 64];
-  __shared__ __attribute__((aligned(1024))) char sS1[SBYTES + 64];
-  __shared__ __attribute__((aligned(1024))) char sS2[SBYTES + 64];
-  __shared__ __attribute__((aligned(1024))) char sS3[NS > 3 ? SBYTES + 64 : 64];
+  __shared__ __attribute__((aligned(1024))) char sS0[NP * SREG];
+  __shared__ __attribute__((aligned(1024))) char sS1[NP * SREG];
+  __shared__ __attribute__((aligned(1024))) char sS2[NP * SREG];
+  __shared__ __attribute__((aligned(1024))) char sS3[NS > 3 ? NP * SREG : 64];
   static_assert(NS == 3 || NS == 4, "ring depth");
+  static_assert(SMALL_KMAJOR || NP == 1, "shared-input form exists for the k-major operand only");
   char* const sX[4] = {sX0, sX1, sX2, sX3};
   char* const sS[4] = {sS0, sS1, sS2, sS3};
 
+  const bf16* __restrict__ In = ra.In;
+  const int inner = ra.inner;
   int b = blockIdx.x, k = 0;
-  for (; k < st.K; ++k) {
-    const int nb = (st.off[k + 1] - st.off[k] + TM - 1) / TM;
+  for (; k < ra.K; ++k) {
+    const int nb = (ra.off[k + 1] - ra.off[k] + TM - 1) / TM;
     if (b < nb) break;
     b -= nb;
   }
-  if (k >= st.K) return;
-  const int lo = st.off[k] + b * TM;
-  const int hi = (st.off[k + 1] < lo + TM) ? st.off[k + 1] : lo + TM;
-  const int r = st.rank[k];
-  const float s = st.s[k];
-  const bf16* Mk = static_cast<const bf16*>(Mp.p[k]);
+  if (k >= ra.K) return;
+  const int lo = ra.off[k] + b * TM;
+  const int hi = (ra.off[k + 1] < lo + TM) ? ra.off[k + 1] : lo + TM;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (tid < 16) {
 #pragma unroll
-    for (int s_ = 0; s_ < NS; ++s_) reinterpret_cast<int*>(sS[s_] + SBYTES)[tid] = 0;
+    for (int s_ = 0; s_ < NS; ++s_)
+#pragma unroll
+      for (int p = 0; p < NP; ++p) reinterpret_cast<int*>(sS[s_] + p * SREG + SBYTES)[tid] = 0;
   }
 
   const bf16* xptr[4];
@@ -76,34 +110,44 @@ __global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const bf16* __restrict_
     row = row < hi ? row : hi - 1;
     xptr[it] = In + (size_t)row * inner + c * 8;
   }
-  const int pieces = r / 8;  // 1 KiB pieces of the small operand's tile
-  const bf16* sptr[SPW];
+  int r[NP];
+  size_t sstep[NP];
+  const bf16* sptr[NP][SPW];
 #pragma unroll
-  for (int it = 0; it < SPW; ++it) {
-    // pieces beyond the operand's rank re-fetch piece 0 into their own (never read) slot, so
-    // that every wave issues the same number of loads per tile
-    const int piece = (wave + NWV * it) < pieces ? (wave + NWV * it) : 0;
-    if (SMALL_KMAJOR) {
-      sptr[it] = Mk + piece * 512 + lane * 8;
-    } else {
-      int q = 8 * piece + (lane >> 3);
-      const int c = (lane & 7) ^ ((q >> 1) & 7);
-      q = q < r ? q : r - 1;
-      sptr[it] = Mk + (size_t)q * inner + c * 8;
+  for (int p = 0; p < NP; ++p) {
+    r[p] = ra.rank[p][k];
+    const bf16* Mk = static_cast<const bf16*>(ra.M[p].p[k]);
+    const int pieces = r[p] / 8;  // 1 KiB pieces of the small operand's tile
+#pragma unroll
+    for (int it = 0; it < SPW; ++it) {
+      // pieces beyond the operand's rank re-fetch piece 0 into their own (never read) slot, so
+      // that every wave issues the same number of loads per tile
+      const int piece = (wave + NWV * it) < pieces ? (wave + NWV * it) : 0;
+      if (SMALL_KMAJOR) {
+        sptr[p][it] = Mk + piece * 512 + lane * 8;
+      } else {
+        int q = 8 * piece + (lane >> 3);
+        const int c = (lane & 7) ^ ((q >> 1) & 7);
+        q = q < r[p] ? q : r[p] - 1;
+        sptr[p][it] = Mk + (size_t)q * inner + c * 8;
+      }
     }
+    sstep[p] = SMALL_KMAJOR ? (size_t)64 * r[p] : (size_t)64;
   }
-  const size_t sstep = SMALL_KMAJOR ? (size_t)64 * r : (size_t)64;
 
   auto issue = [&](int kt, char* sx, char* ss) {
 #pragma unroll
     for (int it = 0; it < 4; ++it) load_lds_16B(xptr[it] + (size_t)kt * 64, sx + (wave + NWV * it) * 1024);
 #pragma unroll
-    for (int it = 0; it < SPW; ++it)
-      if (wave + NWV * it < 4 * NQ) load_lds_16B(sptr[it] + (size_t)kt * sstep, ss + (wave + NWV * it) * 1024);
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+      for (int it = 0; it < SPW; ++it)
+        load_lds_16B(sptr[p][it] + (size_t)kt * sstep[p], ss + p * SREG + (wave + NWV * it) * 1024);
   };
-  // loads per wave per tile; the same for every wave when NWV divides 4 NQ (it always does here)
+  // loads per wave per tile; the same for every wave because NWV divides 4 NQ
   static_assert((4 * NQ) % NWV == 0, "small-operand pieces must split evenly over the waves");
-  constexpr int PER_TILE = 4 + SPW;
+  constexpr int PER_TILE = 4 + NP * SPW;
+  static_assert((NS - 2) * PER_TILE < 64, "vmcnt range");
 
   const int l32 = lane & 31, lhi = lane >> 5;
   const int fsw = (l32 >> 1) & 7;
@@ -111,31 +155,37 @@ __global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const bf16* __restrict_
   const int tr_k = 8 * (blk >> 1) + kq;
   const int tr_n = 16 * (blk & 1) + 4 * (L16 & 3);
 
-  f32x16 acc[NQ];
+  f32x16 acc[NP][NQ];
 #pragma unroll
-  for (int j = 0; j < NQ; ++j)
+  for (int p = 0; p < NP; ++p)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    for (int j = 0; j < NQ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[p][j][e] = 0.f;
 
-  auto compute = [&](const char* sx, const char* ss) {
+  auto compute = [&](const char* sx, const char* ssall) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int coff = ((2 * ks + lhi) ^ fsw) << 4;
       const bf16x8 xf = *(const bf16x8*)(sx + (32 * wave + l32) * 128 + coff);
 #pragma unroll
-      for (int j = 0; j < NQ; ++j) {
-        if (32 * j < r) {
-          bf16x8 sf;
-          if (SMALL_KMAJOR) {
-            const int n = 32 * j + tr_n;
-            const int kk = 16 * ks + tr_k;
-            const char* p0 = ss + ((n < r) ? (kk * r + n) * 2 : SBYTES);
-            const char* p1 = ss + ((n < r) ? ((kk + 4) * r + n) * 2 : SBYTES);
-            sf = join(lds_read_tr(p0), lds_read_tr(p1));
-          } else {
-            sf = *(const bf16x8*)(ss + (32 * j + l32) * 128 + coff);
+      for (int p = 0; p < NP; ++p) {
+        const char* ss = ssall + p * SREG;
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+          if (32 * j < r[p]) {
+            bf16x8 sf;
+            if (SMALL_KMAJOR) {
+              const int n = 32 * j + tr_n;
+              const int kk = 16 * ks + tr_k;
+              const char* p0 = ss + ((n < r[p]) ? (kk * r[p] + n) * 2 : SBYTES);
+              const char* p1 = ss + ((n < r[p]) ? ((kk + 4) * r[p] + n) * 2 : SBYTES);
+              sf = join(lds_read_tr(p0), lds_read_tr(p1));
+            } else {
+              sf = *(const bf16x8*)(ss + (32 * j + l32) * 128 + coff);
+            }
+            acc[p][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, xf, acc[p][j], 0, 0, 0);
           }
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, xf, acc[j], 0, 0, 0);
         }
       }
     }
@@ -170,15 +220,21 @@ __global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const bf16* __restrict_
   const int row = lo + 32 * wave + l32;
   if (row < hi) {
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
+    for (int p = 0; p < NP; ++p) {
+      const float s = ra.s[p][k];
+      const int ldz = ra.ldz[p];
+      bf16* __restrict__ Out = ra.Out[p];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int q = 32 * j + 8 * g + 4 * lhi;
-        if (q < ldz) {
-          bf16x4 o;
+      for (int j = 0; j < NQ; ++j) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16>((q + e < r) ? acc[j][4 * g + e] * s : 0.f);
-          *(bf16x4*)(Out + (size_t)row * ldz + q) = o;
+        for (int g = 0; g < 4; ++g) {
+          const int q = 32 * j + 8 * g + 4 * lhi;
+          if (q < ldz) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16>((q + e < r[p]) ? acc[p][j][4 * g + e] * s : 0.f);
+            *(bf16x4*)(Out + (size_t)row * ldz + q) = o;
+          }
         }
       }
     }
@@ -187,41 +243,44 @@ __global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const bf16* __restrict_
 
 // ------------------------------------------------------------------------------------------
 // Gradient products whose contraction runs over the tokens of one task:
-//   WIDE_FIRST = true : out_k[p, q] (+)= sum_t Big[t, p] * Small[t, q]   (dA_k = x_k^T G,  out row stride r_k)
-//   WIDE_FIRST = false: out_k[q, j] (+)= sum_t Small[t, q] * Big[t, j]   (dB_k = Z^T dy_k, out row stride wide)
-// Big is [T, wide] (X or dY), Small is [T, ldz] (G or Z, zero in columns >= r_k).
+//   WIDE_FIRST = true : out_pk[c, q] (+)= sum_t Big[t, c] * Small_p[t, q]   (dA_k = x_k^T G,  out row stride r_k)
+//   WIDE_FIRST = false: out_k[q, j]  (+)= sum_t Small[t, q] * Big[t, j]     (dB_k = Z^T dy_k, out row stride wide)
+// Big is [T, wide] (X or dY), Small_p is [T, ldz_p] (G or Z, zero in columns >= r_pk).
 // Block: one task, 128 columns of Big, all its tokens in tiles of 64; 4 waves x 32 columns.
 // The whole reduction of an output element happens inside one block: deterministic, no atomics.
 // ------------------------------------------------------------------------------------------
-template <bool WIDE_FIRST, int NQ, int NS>
-__global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big, int wide, int T,
-                                                   const bf16* __restrict__ Small, int ldz, SegTable st,
-                                                   OutTable out, int accumulate, int chunks) {
+template <bool WIDE_FIRST, int NQ, int NS, int NP>
+__global__ __launch_bounds__(256) void k_grad_mfma(const GradArgs<NP> ga) {
   constexpr int WC = 128;
   constexpr int SBYTES = NQ * 32 * 128;  // 64 tokens x ldz x 2 B, ldz <= 32 NQ
+  // a small-operand tile is followed by 64 zero bytes: where lanes beyond the tile's columns point
+  constexpr int SREG = SBYTES + 1024;    // per projection; keeps every 1 KiB load slot aligned
   __shared__ __attribute__((aligned(1024))) char sB0[64 * WC * 2];
   __shared__ __attribute__((aligned(1024))) char sB1[64 * WC * 2];
   __shared__ __attribute__((aligned(1024))) char sB2[64 * WC * 2];
   __shared__ __attribute__((aligned(1024))) char sB3[NS > 3 ? 64 * WC * 2 : 16];
-  // 64 zero bytes behind each small-operand tile: where lanes beyond the tile's columns point
-  __shared__ __attribute__((aligned(1024))) char sS0[SBYTES + 64];
-  __shared__ __attribute__((aligned(1024))) char sS1[SBYTES + 64];
-  __shared__ __attribute__((aligned(1024))) char sS2[SBYTES + 64];
-  __shared__ __attribute__((aligned(1024))) char sS3[NS > 3 ? SBYTES + 64 : 64];
+  __shared__ __attribute__((aligned(1024))) char sS0[NP * SREG];
+  __shared__ __attribute__((aligned(1024))) char sS1[NP * SREG];
+  __shared__ __attribute__((aligned(1024))) char sS2[NP * SREG];
+  __shared__ __attribute__((aligned(1024))) char sS3[NS > 3 ? NP * SREG : 64];
   static_assert(NS == 3 || NS == 4, "ring depth");
+  static_assert(WIDE_FIRST || NP == 1, "shared-input form exists for dA only");
   char* const sB[4] = {sB0, sB1, sB2, sB3};
   char* const sS[4] = {sS0, sS1, sS2, sS3};
 
-  const int k = blockIdx.x / chunks, ch = blockIdx.x % chunks;
+  const bf16* __restrict__ Big = ga.Big;
+  const int wide = ga.wide, T = ga.T;
+  const int k = blockIdx.x / ga.chunks, ch = blockIdx.x % ga.chunks;
   const int col0 = ch * WC;
-  const int lo = st.off[k], hi = st.off[k + 1];
+  const int lo = ga.off[k], hi = ga.off[k + 1];
   const int tk = hi - lo;
-  const int r = st.rank[k];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (tid < 16) {
 #pragma unroll
-    for (int s_ = 0; s_ < NS; ++s_) reinterpret_cast<int*>(sS[s_] + SBYTES)[tid] = 0;
+    for (int s_ = 0; s_ < NS; ++s_)
+#pragma unroll
+      for (int p = 0; p < NP; ++p) reinterpret_cast<int*>(sS[s_] + p * SREG + SBYTES)[tid] = 0;
   }
 
   // Big tile: 64 token rows x 256 B; wave instruction w covers rows 4w..4w+3
@@ -235,20 +294,25 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
     brow[it] = rl;
     bcol[it] = col;
   }
-  // Small tile: 64 tokens x ldz, contiguous in memory; piece = 1 KiB = 64 chunks of 16 B
-  const int cpr = ldz / 8;  // chunks per token row
-  const int pieces = ldz / 8;
-  int srow[NQ], scol[NQ];
+  // Small tiles: 64 tokens x ldz_p, contiguous in memory; piece = 1 KiB = 64 chunks of 16 B
+  int ldz[NP];
+  int srow[NP][NQ], scol[NP][NQ];
 #pragma unroll
-  for (int it = 0; it < NQ; ++it) {
-    // pieces beyond the tile re-fetch piece 0 into their own (never read) slot, so that every
-    // wave issues the same number of loads per tile
-    const int piece = (wave + 4 * it) < pieces ? (wave + 4 * it) : 0;
-    const int chunk = piece * 64 + lane;
-    srow[it] = chunk / cpr;
-    scol[it] = (chunk % cpr) * 8;
+  for (int p = 0; p < NP; ++p) {
+    ldz[p] = ga.ldz[p];
+    const int cpr = ldz[p] / 8;  // chunks per token row = 1 KiB pieces per tile
+#pragma unroll
+    for (int it = 0; it < NQ; ++it) {
+      // pieces beyond the tile re-fetch piece 0 into their own (never read) slot, so that every
+      // wave issues the same number of loads per tile
+      const int piece = (wave + 4 * it) < cpr ? (wave + 4 * it) : 0;
+      const int chunk = piece * 64 + lane;
+      srow[p][it] = chunk / cpr;
+      scol[p][it] = (chunk % cpr) * 8;
+    }
   }
-  constexpr int PER_TILE = 4 + NQ;
+  constexpr int PER_TILE = 4 + NP * NQ;
+  static_assert((NS - 2) * PER_TILE < 64, "vmcnt range");
 
   auto issue = [&](int kt, char* sb, char* ss) {
     const int t0 = lo + kt * 64;
@@ -259,11 +323,13 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
       load_lds_16B(Big + (size_t)tok * wide + bcol[it], sb + (wave + 4 * it) * 1024);
     }
 #pragma unroll
-    for (int it = 0; it < NQ; ++it) {
-      int tok = t0 + srow[it];
-      tok = tok < T ? tok : T - 1;
-      load_lds_16B(Small + (size_t)tok * ldz + scol[it], ss + (wave + 4 * it) * 1024);
-    }
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+      for (int it = 0; it < NQ; ++it) {
+        int tok = t0 + srow[p][it];
+        tok = tok < T ? tok : T - 1;
+        load_lds_16B(ga.Small[p] + (size_t)tok * ldz[p] + scol[p][it], ss + p * SREG + (wave + 4 * it) * 1024);
+      }
   };
 
   const int l32 = lane & 31, lhi = lane >> 5;
@@ -273,39 +339,45 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
   const int wide_n = 32 * wave + tr_n;
   const int wide_off = (((wide_n >> 3) ^ (kq << 2)) << 4) + (wide_n & 7) * 2;
 
-  f32x16 acc[NQ];
+  f32x16 acc[NP][NQ];
 #pragma unroll
-  for (int j = 0; j < NQ; ++j)
+  for (int p = 0; p < NP; ++p)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    for (int j = 0; j < NQ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[p][j][e] = 0.f;
 
   // `valid` = number of tokens of this tile that belong to the task (64 except in the last tile)
-  auto compute = [&](const char* sb, const char* ss, int valid) {
+  auto compute = [&](const char* sb, const char* ssall, int valid) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int kk = 16 * ks + tr_k;
       const bf16x8 wf = join(lds_read_tr(sb + kk * 256 + wide_off), lds_read_tr(sb + (kk + 4) * 256 + wide_off));
 #pragma unroll
-      for (int j = 0; j < NQ; ++j) {
-        if (32 * j < ldz) {
-          const int n = 32 * j + tr_n;
-          const char* p0 = ss + ((n < ldz) ? (kk * ldz + n) * 2 : SBYTES);
-          const char* p1 = ss + ((n < ldz) ? ((kk + 4) * ldz + n) * 2 : SBYTES);
-          short4v s0 = lds_read_tr(p0), s1 = lds_read_tr(p1);
-          if (valid < 64) {
-            // the lane's 8 contraction indices are tokens 16ks + 8*lhi + 0..7 of the tile
-            const int tbase = 16 * ks + 8 * lhi;
+      for (int p = 0; p < NP; ++p) {
+        const char* ss = ssall + p * SREG;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              if (tbase + e >= valid) s0[e] = 0;
-              if (tbase + 4 + e >= valid) s1[e] = 0;
+        for (int j = 0; j < NQ; ++j) {
+          if (32 * j < ldz[p]) {
+            const int n = 32 * j + tr_n;
+            const char* p0 = ss + ((n < ldz[p]) ? (kk * ldz[p] + n) * 2 : SBYTES);
+            const char* p1 = ss + ((n < ldz[p]) ? ((kk + 4) * ldz[p] + n) * 2 : SBYTES);
+            short4v s0 = lds_read_tr(p0), s1 = lds_read_tr(p1);
+            if (valid < 64) {
+              // the lane's 8 contraction indices are tokens 16ks + 8*lhi + 0..7 of the tile
+              const int tbase = 16 * ks + 8 * lhi;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                if (tbase + e >= valid) s0[e] = 0;
+                if (tbase + 4 + e >= valid) s1[e] = 0;
+              }
             }
+            const bf16x8 sf = join(s0, s1);
+            if (WIDE_FIRST)
+              acc[p][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, sf, acc[p][j], 0, 0, 0);
+            else
+              acc[p][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, wf, acc[p][j], 0, 0, 0);
           }
-          const bf16x8 sf = join(s0, s1);
-          if (WIDE_FIRST)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, sf, acc[j], 0, 0, 0);
-          else
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, wf, acc[j], 0, 0, 0);
         }
       }
     }
@@ -333,59 +405,55 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const bf16* __restrict__ Big,
     }
   }
 
-  float* o = out.p[k];
-  if (WIDE_FIRST) {
-    // D[i = column p of Big][j = q]: lane holds q = 32j + l32 and p = col0 + 32*wave + 8g + 4*lhi + e
+  const int accumulate = ga.accumulate;
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
-      const int q = 32 * j + l32;
-      if (q < r) {
+  for (int p = 0; p < NP; ++p) {
+    float* o = ga.out[p].p[k];
+    const int r = ga.rank[p][k];
+    if (WIDE_FIRST) {
+      // D[i = column c of Big][j = q]: lane holds q = 32j + l32 and c = col0 + 32*wave + 8g + 4*lhi + e
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+      for (int j = 0; j < NQ; ++j) {
+        const int q = 32 * j + l32;
+        if (q < r) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int p = col0 + 32 * wave + 8 * g + 4 * lhi + e;
-            if (p < wide) {
-              float* dst = o + (size_t)p * r + q;
-              *dst = accumulate ? *dst + acc[j][4 * g + e] : acc[j][4 * g + e];
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int c = col0 + 32 * wave + 8 * g + 4 * lhi + e;
+              if (c < wide) {
+                float* dst = o + (size_t)c * r + q;
+                *dst = accumulate ? *dst + acc[p][j][4 * g + e] : acc[p][j][4 * g + e];
+              }
             }
-          }
+        }
       }
-    }
-  } else {
-    // D[i = q][j = column of Big]: lane holds column col0 + 32*wave + l32 and q = 32j + 8g + 4*lhi + e
-    const int col = col0 + 32 * wave + l32;
-    if (col < wide) {
+    } else {
+      // D[i = q][j = column of Big]: lane holds column col0 + 32*wave + l32 and q = 32j + 8g + 4*lhi + e
+      const int col = col0 + 32 * wave + l32;
+      if (col < wide) {
 #pragma unroll
-      for (int j = 0; j < NQ; ++j)
+        for (int j = 0; j < NQ; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+          for (int g = 0; g < 4; ++g)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int q = 32 * j + 8 * g + 4 * lhi + e;
-            if (q < r) {
-              float* dst = o + (size_t)q * wide + col;
-              *dst = accumulate ? *dst + acc[j][4 * g + e] : acc[j][4 * g + e];
+            for (int e = 0; e < 4; ++e) {
+              const int q = 32 * j + 8 * g + 4 * lhi + e;
+              if (q < r) {
+                float* dst = o + (size_t)q * wide + col;
+                *dst = accumulate ? *dst + acc[p][j][4 * g + e] : acc[p][j][4 * g + e];
+              }
             }
-          }
+      }
     }
   }
 }
 
-// Ring depth: three stages (two tiles in flight) keep a block at 72 KiB of LDS for ranks up to 64,
+// Ring depth: three stages (two tiles in flight) keep a block at 75 KiB of LDS for ranks up to 64,
 // so two blocks share a CU; measured 8 % faster than four stages with one block per CU.
 constexpr int kRing = 3;
 
-template <bool KMAJOR, int TM, int NS>
-void launch_rows_tm(int nq, dim3 grid, hipStream_t s, const bf16* In, int inner, bf16* Out, int ldz, const SegTable& st,
-                    const PtrTable& M) {
-  if (nq == 1)
-    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 1, NS, TM>), grid, dim3(TM * 2), 0, s, In, inner, Out, ldz, st, M);
-  else if (nq == 2)
-    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 2, NS, TM>), grid, dim3(TM * 2), 0, s, In, inner, Out, ldz, st, M);
-  else
-    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, 4, NS, TM>), grid, dim3(TM * 2), 0, s, In, inner, Out, ldz, st, M);
-}
+int nq_of(int ldz) { return ldz <= 32 ? 1 : (ldz <= 64 ? 2 : 4); }
 
 int row_blocks(const SegTable& st, int tm) {
   int blocks = 0;
@@ -393,61 +461,170 @@ int row_blocks(const SegTable& st, int tm) {
   return blocks;
 }
 
-template <bool WIDE_FIRST>
-void launch_grad(int nq, dim3 grid, hipStream_t s, const bf16* Big, int wide, int T, const bf16* Small, int ldz,
-                 const SegTable& st, const OutTable& out, int accumulate, int chunks) {
-  if (nq == 1)
-    hipLaunchKernelGGL((k_grad_mfma<WIDE_FIRST, 1, kRing>), grid, dim3(256), 0, s, Big, wide, T, Small, ldz, st, out,
-                       accumulate, chunks);
-  else if (nq == 2)
-    hipLaunchKernelGGL((k_grad_mfma<WIDE_FIRST, 2, kRing>), grid, dim3(256), 0, s, Big, wide, T, Small, ldz, st, out,
-                       accumulate, chunks);
-  else
-    hipLaunchKernelGGL((k_grad_mfma<WIDE_FIRST, 4, kRing>), grid, dim3(256), 0, s, Big, wide, T, Small, ldz, st, out,
-                       accumulate, chunks);
+// the largest row tile that still gives every CU (256) a block: at equal block counts the
+// larger tile is faster (fewer fetches of the small operand per row)
+int pick_row_tile(const SegTable& st) {
+  int tm = 128;
+  if (row_blocks(st, tm) < 256) tm = 64;
+  if (tm == 64 && row_blocks(st, tm) < 256) tm = 32;
+  return tm;
 }
 
-int nq_of(int ldz) { return ldz <= 32 ? 1 : (ldz <= 64 ? 2 : 4); }
+template <bool KMAJOR, int NQ, int TM, int NP>
+hipError_t launch_rows_one(const RowsArgs<NP>& a, int blocks, hipStream_t s) {
+  if constexpr (NP * NQ <= 8) {
+    hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, NQ, kRing, TM, NP>), dim3(blocks), dim3(TM * 2), 0, s, a);
+    return hipGetLastError();
+  } else {
+    return hipErrorInvalidValue;
+  }
+}
+
+template <bool KMAJOR, int NQ, int NP>
+hipError_t launch_rows_tm(const RowsArgs<NP>& a, int tm, int blocks, hipStream_t s) {
+  if (tm == 128) return launch_rows_one<KMAJOR, NQ, 128, NP>(a, blocks, s);
+  if (tm == 64) return launch_rows_one<KMAJOR, NQ, 64, NP>(a, blocks, s);
+  return launch_rows_one<KMAJOR, NQ, 32, NP>(a, blocks, s);
+}
+
+template <bool KMAJOR, int NP>
+hipError_t launch_rows(const RowsArgs<NP>& a, int nq, int tm, int blocks, hipStream_t s) {
+  if (nq == 1) return launch_rows_tm<KMAJOR, 1, NP>(a, tm, blocks, s);
+  if (nq == 2) return launch_rows_tm<KMAJOR, 2, NP>(a, tm, blocks, s);
+  return launch_rows_tm<KMAJOR, 4, NP>(a, tm, blocks, s);
+}
+
+template <bool WIDE_FIRST, int NQ, int NP>
+hipError_t launch_grad_one(const GradArgs<NP>& a, int blocks, hipStream_t s) {
+  if constexpr (NP * NQ <= 8) {
+    hipLaunchKernelGGL((k_grad_mfma<WIDE_FIRST, NQ, kRing, NP>), dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+  } else {
+    return hipErrorInvalidValue;
+  }
+}
+
+template <bool WIDE_FIRST, int NP>
+hipError_t launch_grad(const GradArgs<NP>& a, int nq, int blocks, hipStream_t s) {
+  if (nq == 1) return launch_grad_one<WIDE_FIRST, 1, NP>(a, blocks, s);
+  if (nq == 2) return launch_grad_one<WIDE_FIRST, 2, NP>(a, blocks, s);
+  return launch_grad_one<WIDE_FIRST, 4, NP>(a, blocks, s);
+}
+
+template <int NP>
+hipError_t rows_group(const LowrankGroupItem* it, const SegTable& st, const bf16* In, int inner, int nq, hipStream_t s) {
+  RowsArgs<NP> a;
+  a.In = In;
+  a.inner = inner;
+  a.K = st.K;
+  for (int k = 0; k <= kMaxK; ++k) a.off[k] = st.off[k];
+  for (int p = 0; p < NP; ++p) {
+    a.Out[p] = it[p].rows_out;
+    a.ldz[p] = it[p].ldz;
+    for (int k = 0; k < kMaxK; ++k) {
+      a.rank[p][k] = (unsigned char)(k < st.K ? it[p].rank[k] : 0);
+      a.s[p][k] = k < st.K ? it[p].s[k] : 0.f;
+    }
+    a.M[p] = *it[p].M;
+  }
+  const int tm = pick_row_tile(st);
+  const int blocks = row_blocks(st, tm);
+  if (blocks == 0) return hipSuccess;
+  return launch_rows<true, NP>(a, nq, tm, blocks, s);
+}
+
+template <int NP>
+hipError_t grad_group(const LowrankGroupItem* it, const SegTable& st, const bf16* Big, int wide, int T, int nq,
+                      int accumulate, hipStream_t s) {
+  GradArgs<NP> a;
+  a.Big = Big;
+  a.wide = wide;
+  a.T = T;
+  a.K = st.K;
+  for (int k = 0; k <= kMaxK; ++k) a.off[k] = st.off[k];
+  for (int p = 0; p < NP; ++p) {
+    a.Small[p] = it[p].grad_small;
+    a.ldz[p] = it[p].ldz;
+    for (int k = 0; k < kMaxK; ++k) a.rank[p][k] = (unsigned char)(k < st.K ? it[p].rank[k] : 0);
+    a.out[p] = *it[p].grad_out;
+  }
+  a.accumulate = accumulate;
+  a.chunks = (wide + 127) / 128;
+  return launch_grad<true, NP>(a, nq, st.K * a.chunks, s);
+}
 
 }  // namespace
 
 // Z = s x A (a_major = true, M = A_k) or G = s dy B^T (a_major = false, M = B_k).
 hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* Out, const PtrTable& M,
                              bool a_major) {
-  // the largest row tile that still gives every CU (256) a block: at equal block counts the
-  // larger tile is faster (fewer fetches of the small operand per row)
-  int tm = 128;
-  if (row_blocks(c.st, tm) < 256) tm = 64;
-  if (tm == 64 && row_blocks(c.st, tm) < 256) tm = 32;
+  const int tm = pick_row_tile(c.st);
   const int blocks = row_blocks(c.st, tm);
   if (blocks == 0) return hipSuccess;
+  RowsArgs<1> a;
+  a.In = In;
+  a.inner = inner;
+  a.K = c.st.K;
+  for (int k = 0; k <= kMaxK; ++k) a.off[k] = c.st.off[k];
+  a.Out[0] = Out;
+  a.ldz[0] = c.ldz;
+  for (int k = 0; k < kMaxK; ++k) {
+    a.rank[0][k] = (unsigned char)c.st.rank[k];
+    a.s[0][k] = c.st.s[k];
+  }
+  a.M[0] = M;
   const int nq = nq_of(c.ldz);
-  const dim3 grid(blocks);
-#define MLORA_ROWS(KM)                                                                           \
-  do {                                                                                           \
-    if (tm == 128) launch_rows_tm<KM, 128, kRing>(nq, grid, c.stream, In, inner, Out, c.ldz, c.st, M);     \
-    else if (tm == 64) launch_rows_tm<KM, 64, kRing>(nq, grid, c.stream, In, inner, Out, c.ldz, c.st, M);  \
-    else launch_rows_tm<KM, 32, kRing>(nq, grid, c.stream, In, inner, Out, c.ldz, c.st, M);                \
-  } while (0)
-  if (a_major)
-    MLORA_ROWS(true);
-  else
-    MLORA_ROWS(false);
-#undef MLORA_ROWS
-  return hipGetLastError();
+  return a_major ? launch_rows<true, 1>(a, nq, tm, blocks, c.stream) : launch_rows<false, 1>(a, nq, tm, blocks, c.stream);
 }
 
 // dA_k = x_k^T G (wide_first = true; Big = X [T,h], Small = G) or dB_k = Z^T dy_k (Big = dY [T,d], Small = Z).
 hipError_t grad_mfma(const CallCtx& c, const bf16* Big, int wide, const bf16* Small, const OutTable& out,
                      int accumulate, bool wide_first) {
   if (c.K == 0) return hipSuccess;
-  const int chunks = (wide + 127) / 128;
-  const dim3 grid(c.K * chunks);
-  if (wide_first)
-    launch_grad<true>(nq_of(c.ldz), grid, c.stream, Big, wide, c.T, Small, c.ldz, c.st, out, accumulate, chunks);
-  else
-    launch_grad<false>(nq_of(c.ldz), grid, c.stream, Big, wide, c.T, Small, c.ldz, c.st, out, accumulate, chunks);
-  return hipGetLastError();
+  GradArgs<1> a;
+  a.Big = Big;
+  a.wide = wide;
+  a.T = c.T;
+  a.K = c.st.K;
+  for (int k = 0; k <= kMaxK; ++k) a.off[k] = c.st.off[k];
+  a.Small[0] = Small;
+  a.ldz[0] = c.ldz;
+  for (int k = 0; k < kMaxK; ++k) a.rank[0][k] = (unsigned char)c.st.rank[k];
+  a.out[0] = out;
+  a.accumulate = accumulate;
+  a.chunks = (wide + 127) / 128;
+  const int nq = nq_of(c.ldz);
+  const int blocks = c.K * a.chunks;
+  return wide_first ? launch_grad<true, 1>(a, nq, blocks, c.stream) : launch_grad<false, 1>(a, nq, blocks, c.stream);
+}
+
+// Whether np projections whose widest low-rank row stride is max_ldz fit the shared-input kernels
+// (accumulators: np x ceil(max_ldz / 32) MFMA column groups, at most 8).
+bool lowrank_group_ok(int np, int max_ldz) { return np >= 2 && np <= 4 && np * nq_of(max_ldz) <= 8; }
+
+// Z_p = s_pk x_k A_pk for np projections in one pass over X.
+hipError_t lowrank_rows_mfma_group(int np, const LowrankGroupItem* items, const SegTable& st, const bf16* X, int h,
+                                   hipStream_t stream) {
+  int mx = 0;
+  for (int p = 0; p < np; ++p) mx = items[p].ldz > mx ? items[p].ldz : mx;
+  if (!lowrank_group_ok(np, mx)) return hipErrorInvalidValue;
+  const int nq = nq_of(mx);
+  if (np == 2) return rows_group<2>(items, st, X, h, nq, stream);
+  if (np == 3) return rows_group<3>(items, st, X, h, nq, stream);
+  return rows_group<4>(items, st, X, h, nq, stream);
+}
+
+// dA_pk = x_k^T G_p for np projections in one pass over X.
+hipError_t grad_mfma_group(int np, const LowrankGroupItem* items, const SegTable& st, const bf16* X, int h, int T,
+                           int accumulate, hipStream_t stream) {
+  if (st.K == 0) return hipSuccess;
+  int mx = 0;
+  for (int p = 0; p < np; ++p) mx = items[p].ldz > mx ? items[p].ldz : mx;
+  if (!lowrank_group_ok(np, mx)) return hipErrorInvalidValue;
+  const int nq = nq_of(mx);
+  if (np == 2) return grad_group<2>(items, st, X, h, T, nq, accumulate, stream);
+  if (np == 3) return grad_group<3>(items, st, X, h, T, nq, accumulate, stream);
+  return grad_group<4>(items, st, X, h, T, nq, accumulate, stream);
 }
 
 }  // namespace mlora

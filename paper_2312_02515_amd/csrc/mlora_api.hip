@@ -97,13 +97,18 @@ hipError_t compute_Z(const mlora_problem* p, const CallCtx& c, const void* X, vo
   return generic_Z(c, X, Z);
 }
 
-hipError_t forward_impl(const mlora_problem* p, const CallCtx& c, const void* X, void* Y, void* Z) {
-  hipError_t e = compute_Z(p, c, X, Z);
-  if (e != hipSuccess) return e;
+// Y = X W + Z B_k, given Z
+hipError_t forward_gemm(const mlora_problem* p, const CallCtx& c, const void* X, void* Y, const void* Z) {
   if (mfma_gemm_applies(p) && aligned16(X) && aligned16(Y) && aligned16(Z))
     return gemm_mfma((const bf16*)X, (const bf16*)p->W, (bf16*)Y, c.T, c.d, c.h, true, (const bf16*)Z, c.ldz, c.st, c.B,
                      c.stream);
   return generic_gemm_fwd(c, X, Y, Z);
+}
+
+hipError_t forward_impl(const mlora_problem* p, const CallCtx& c, const void* X, void* Y, void* Z) {
+  hipError_t e = compute_Z(p, c, X, Z);
+  if (e != hipSuccess) return e;
+  return forward_gemm(p, c, X, Y, Z);
 }
 
 mlora_status check_grad_tables(const mlora_problem* p, float* const* dA, float* const* dB) {
@@ -116,8 +121,9 @@ mlora_status check_grad_tables(const mlora_problem* p, float* const* dA, float* 
 }
 
 // G, dB_k and dA_k, given Z
+// (with `skip_dA` the caller computes dA_k itself from G)
 hipError_t adapter_grads_impl(const mlora_problem* p, const CallCtx& c, const void* X, const void* dY, const void* Z,
-                              void* G, float* const* dA, float* const* dB, int accumulate) {
+                              void* G, float* const* dA, float* const* dB, int accumulate, bool skip_dA = false) {
   OutTable ta, tb;
   for (int k = 0; k < kMaxK; ++k) {
     ta.p[k] = k < p->K ? dA[k] : nullptr;
@@ -127,11 +133,11 @@ hipError_t adapter_grads_impl(const mlora_problem* p, const CallCtx& c, const vo
   if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(dY) && aligned16(Z) && aligned16(G)) {
     e = lowrank_rows_mfma(c, (const bf16*)dY, c.d, (bf16*)G, c.B, false);
     if (e == hipSuccess) e = grad_mfma(c, (const bf16*)dY, c.d, (const bf16*)Z, tb, accumulate ? 1 : 0, false);
-    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)X, c.h, (const bf16*)G, ta, accumulate ? 1 : 0, true);
+    if (e == hipSuccess && !skip_dA) e = grad_mfma(c, (const bf16*)X, c.h, (const bf16*)G, ta, accumulate ? 1 : 0, true);
   } else {
     e = generic_G(c, dY, G);
     if (e == hipSuccess) e = generic_dB(c, Z, dY, tb, accumulate ? 1 : 0);
-    if (e == hipSuccess) e = generic_dA(c, X, G, ta, accumulate ? 1 : 0);
+    if (e == hipSuccess && !skip_dA) e = generic_dA(c, X, G, ta, accumulate ? 1 : 0);
   }
   return e;
 }
@@ -148,6 +154,18 @@ hipError_t backward_impl(const mlora_problem* p, const CallCtx& c, const void* X
       e = generic_gemm_bwd(c, dY, dX, G);
   }
   return e;
+}
+
+// Whether the shared-input low-rank kernels (one pass over X for all projections) apply
+bool group_lowrank_applies(const mlora_problem* const* ps, int P, const void* X) {
+  if (P < 2 || !aligned16(X)) return false;
+  int mx = 0;
+  for (int p = 0; p < P; ++p) {
+    if (!mfma_lowrank_applies(ps[p])) return false;
+    const int l = lowrank_ld(ps[p]);
+    mx = l > mx ? l : mx;
+  }
+  return lowrank_group_ok(P, mx);
 }
 
 // A group is valid when each member is and all share T, h, K, the dtype and the split positions.
@@ -270,10 +288,23 @@ mlora_status mlora_lora_group_fwd(const mlora_problem* const* ps, int P, const v
   for (int p = 0; p < P; ++p)
     if (Y[p] == nullptr || saved[p] == nullptr) return MLORA_ERR_NULL;
   if (workspace == nullptr || workspace_bytes < mlora_lora_group_workspace_bytes(ps, P)) return MLORA_ERR_WORKSPACE;
+  CallCtx c[MLORA_MAX_GROUP];
+  bool fused = group_lowrank_applies(ps, P, X);
   for (int p = 0; p < P; ++p) {
-    CallCtx c;
-    fill_ctx(ps[p], hip_stream, &c);
-    hipError_t e = forward_impl(ps[p], c, X, Y[p], saved[p]);
+    fill_ctx(ps[p], hip_stream, &c[p]);
+    fused = fused && aligned16(saved[p]);
+  }
+  if (fused) {
+    // every Z_p in one pass over X
+    LowrankGroupItem it[MLORA_MAX_GROUP];
+    for (int p = 0; p < P; ++p) {
+      it[p] = LowrankGroupItem{c[p].ldz, c[p].st.rank, c[p].st.s, &c[p].A, (bf16*)saved[p], nullptr, nullptr};
+    }
+    hipError_t e = lowrank_rows_mfma_group(P, it, c[0].st, (const bf16*)X, c[0].h, c[0].stream);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  for (int p = 0; p < P; ++p) {
+    hipError_t e = fused ? forward_gemm(ps[p], c[p], X, Y[p], saved[p]) : forward_impl(ps[p], c[p], X, Y[p], saved[p]);
     if (e != hipSuccess) return hip_status(e);
   }
   return MLORA_OK;
@@ -308,9 +339,22 @@ mlora_status mlora_lora_group_bwd(const mlora_problem* const* ps, int P, const v
     w += lowrank_bytes(ps[p]);
     sum_kernel = sum_kernel && mfma_gemm_applies(ps[p]) && aligned16(dY[p]) && aligned16(G[p]);
   }
+  bool fused = ps[0]->K > 0 && group_lowrank_applies(ps, P, X);
+  for (int p = 0; p < P; ++p) fused = fused && aligned16(dY[p]) && aligned16(saved[p]) && aligned16(G[p]);
   for (int p = 0; p < P; ++p) {
     hipError_t e = adapter_grads_impl(ps[p], c[p], X, dY[p], saved[p], G[p], ps[0]->K > 0 ? dA[p] : nullptr,
-                                      ps[0]->K > 0 ? dB[p] : nullptr, accumulate);
+                                      ps[0]->K > 0 ? dB[p] : nullptr, accumulate, fused);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  if (fused) {
+    // every dA_pk in one pass over X
+    OutTable ta[MLORA_MAX_GROUP];
+    LowrankGroupItem it[MLORA_MAX_GROUP];
+    for (int p = 0; p < P; ++p) {
+      for (int k = 0; k < kMaxK; ++k) ta[p].p[k] = k < ps[p]->K ? dA[p][k] : nullptr;
+      it[p] = LowrankGroupItem{c[p].ldz, c[p].st.rank, c[p].st.s, &c[p].A, nullptr, (const bf16*)G[p], &ta[p]};
+    }
+    hipError_t e = grad_mfma_group(P, it, c[0].st, (const bf16*)X, c[0].h, c[0].T, accumulate ? 1 : 0, c[0].stream);
     if (e != hipSuccess) return hip_status(e);
   }
   if (dX == nullptr || ps[0]->T == 0) return MLORA_OK;

@@ -105,4 +105,22 @@ hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* 
 hipError_t grad_mfma(const CallCtx& c, const bf16* Big, int wide, const bf16* Small, const OutTable& out,
                      int accumulate, bool wide_first);
 
+// One projection of a group that shares its input, for the two shared-input kernels:
+// rows: Z_p = s_pk x_k A_pk (M = A_pk, output rows_out [T, ldz]); grad: dA_pk = x_k^T G_p
+// (grad_small = G_p [T, ldz], output table grad_out).
+struct LowrankGroupItem {
+  int ldz;
+  const int* rank;      // K entries
+  const float* s;       // K entries
+  const PtrTable* M;
+  bf16* rows_out;
+  const bf16* grad_small;
+  const OutTable* grad_out;
+};
+bool lowrank_group_ok(int np, int max_ldz);
+hipError_t lowrank_rows_mfma_group(int np, const LowrankGroupItem* items, const SegTable& st, const bf16* X, int h,
+                                   hipStream_t stream);
+hipError_t grad_mfma_group(int np, const LowrankGroupItem* items, const SegTable& st, const bf16* X, int h, int T,
+                           int accumulate, hipStream_t stream);
+
 }  // namespace mlora
