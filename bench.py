@@ -11,6 +11,7 @@ Prints ONE JSON line:
   metric/value   useful TFLOP/s of the whole step (4 T h d + 6 sum t_k r_k (h+d) per projection)
   roofline       the MFMA base-product kernel against the dense bf16 MFMA peak, timed with
                  HIP events recorded by the library on the launch stream during the timed steps
+  roofline_lowrank  the same for the four HBM-bound low-rank kernels against the HBM peak
   cpu_baseline   the CPU fp64 oracle timed on this machine's host cores on a bounded token sample
 """
 import argparse
@@ -24,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 WORKLOAD = "llama2_13b_layer"
 
 
@@ -118,7 +120,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--cpu-tokens", type=int, default=384, help="tokens per adapter in the CPU oracle sample (0 = skip)")
+    ap.add_argument("--cpu-tokens", type=int, default=512, help="tokens per adapter in the CPU oracle sample (0 = skip)")
     ap.add_argument("--no-power", action="store_true", help="skip the amd-smi power/clock sample after the timed region")
     ap.add_argument("--recompute", action="store_true",
                     help="time the activation-recompute pair of entry points (nothing saved between forward and "
@@ -176,14 +178,15 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    mb.profile_gemm(True)
+    mb.profile_kernels(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    mb.profile_gemm(False)
-    gemm_ms, gemm_flops, gemm_launches = mb.profile_gemm_read()
+    mb.profile_kernels(False)
+    prof = mb.profile_kernels_read()
+    gemm_ms, gemm_flops, gemm_launches = prof["gemm"]
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -205,6 +208,13 @@ def main():
                      "share_of_step_time": gemm_ms / args.steps / ms_per_step,
                      "traffic": _traffic_bytes_per_launch()},
     }
+    # the HBM-bound kernels (s x A and s dy B^T: "rows"; dA_k and dB_k: "grad"): algorithmic bytes per
+    # launch (activations read once, results written once) over the HIP-event duration
+    out["roofline_lowrank"] = {
+        kind: {"bound": "hbm", "kernel": kname, "achieved": (by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0),
+               "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": (by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS if ms > 0 else 0.0),
+               "launches": n, "avg_launch_ms": ms / max(n, 1), "share_of_step_time": ms / args.steps / ms_per_step}
+        for kind, kname, (ms, by, n) in (("rows", "k_lowrank_mfma", prof["rows"]), ("grad", "k_grad_mfma", prof["grad"]))}
     if not args.no_power:
         out["power"] = sample_power(step)
     if args.cpu_tokens > 0:

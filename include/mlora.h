@@ -115,6 +115,7 @@ mlora_status mlora_lora_fwd(const mlora_problem* p, const void* X, void* Y, void
  *   accumulate 0: dA_k, dB_k are overwritten (zeros for an empty segment);
  *              1: the gradients are added to what the buffers hold
  * Two tasks must not share a dA or dB buffer.  W is read, never written.
+ * With T == 0 the data pointers may be NULL; overwrite mode still zeroes dA_k, dB_k.
  */
 mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* dY, const void* saved,
                             void* dX, float* const* dA, float* const* dB, int accumulate,
@@ -176,16 +177,24 @@ int mlora_last_hip_error(void);
  * Returns the previous value.  Process-wide. */
 int mlora_set_kernel_path(int path);
 
-/* Measurement aid for the dominant kernel (the MFMA base product with its LoRA steps).
- * While enabled, every launch of that kernel by this process is bracketed by a pair of HIP
- * events recorded on the launch stream (at most 4096 launches are kept; the events are
- * created on first use and live until the process ends).  Returns the previous setting. */
-int mlora_profile_gemm(int enable);
+/* Measurement aid.  While enabled, every launch of the MFMA kernels by this process is bracketed
+ * by a pair of HIP events recorded on the launch stream (at most 16384 launches are kept; the
+ * events are created on first use and live until the process ends).  Returns the previous
+ * setting. */
+int mlora_profile_kernels(int enable);
 
-/* Waits for the recorded launches to finish, returns the sum of their durations in
- * milliseconds, the sum of their algorithmic flops (2 M N K plus 2 t_k r_k N per task) and
- * their count through the non-NULL pointers (HOST), and forgets them. */
-mlora_status mlora_profile_gemm_read(double* ms_total, double* flops_total, int* launches);
+/* Kinds of kernels the measurement aid tells apart, and the unit their work is counted in. */
+#define MLORA_PROFILE_GEMM  0  /* base products with their LoRA steps; algorithmic flops
+                                  (2 M N K plus 2 t_k r_k N per task)                          */
+#define MLORA_PROFILE_ROWS  1  /* s x A and s dy B^T; algorithmic bytes (activation rows read
+                                  once, result written once, adapter matrices read once)       */
+#define MLORA_PROFILE_GRAD  2  /* dA_k and dB_k; algorithmic bytes                             */
+#define MLORA_PROFILE_KINDS 3
+
+/* Waits for the recorded launches to finish; for each kind returns the sum of their durations
+ * in milliseconds, the sum of their work in that kind's unit, and their count, through the
+ * non-NULL pointers (HOST arrays of MLORA_PROFILE_KINDS entries), and forgets them. */
+mlora_status mlora_profile_kernels_read(double* ms_total, double* units_total, int* launches);
 
 #ifdef __cplusplus
 }

@@ -27,8 +27,8 @@ STATUS_NAMES = {0: "MLORA_OK", 1: "MLORA_ERR_NULL", 2: "MLORA_ERR_SHAPE", 3: "ML
 EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_validate", "mlora_lora_fwd",
            "mlora_lora_bwd", "mlora_lora_recompute_workspace_bytes", "mlora_lora_fwd_nosave",
            "mlora_lora_bwd_recompute", "mlora_lora_group_validate", "mlora_lora_group_workspace_bytes",
-           "mlora_lora_group_fwd", "mlora_lora_group_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_gemm",
-           "mlora_profile_gemm_read"]
+           "mlora_lora_group_fwd", "mlora_lora_group_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_kernels",
+           "mlora_profile_kernels_read"]
 
 
 class MloraError(RuntimeError):
@@ -97,11 +97,11 @@ def _load() -> ctypes.CDLL:
     l.mlora_last_hip_error.argtypes = []
     l.mlora_set_kernel_path.restype = ctypes.c_int
     l.mlora_set_kernel_path.argtypes = [ctypes.c_int]
-    l.mlora_profile_gemm.restype = ctypes.c_int
-    l.mlora_profile_gemm.argtypes = [ctypes.c_int]
-    l.mlora_profile_gemm_read.restype = ctypes.c_int
-    l.mlora_profile_gemm_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
-                                          ctypes.POINTER(ctypes.c_int)]
+    l.mlora_profile_kernels.restype = ctypes.c_int
+    l.mlora_profile_kernels.argtypes = [ctypes.c_int]
+    l.mlora_profile_kernels_read.restype = ctypes.c_int
+    l.mlora_profile_kernels_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_int)]
     return l
 
 
@@ -289,14 +289,19 @@ def set_kernel_path(path: int) -> int:
     return int(lib.mlora_set_kernel_path(int(path)))
 
 
-def profile_gemm(enable: bool) -> bool:
-    return bool(lib.mlora_profile_gemm(1 if enable else 0))
+PROFILE_KINDS = ("gemm", "rows", "grad")
 
 
-def profile_gemm_read():
-    """(total ms, total algorithmic flops, launches) of the MFMA base-product kernel since the last read."""
-    ms, fl, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int(0)
-    st = lib.mlora_profile_gemm_read(ctypes.byref(ms), ctypes.byref(fl), ctypes.byref(n))
+def profile_kernels(enable: bool) -> bool:
+    return bool(lib.mlora_profile_kernels(1 if enable else 0))
+
+
+def profile_kernels_read():
+    """{kind: (total ms, total algorithmic units, launches)} of the MFMA kernels since the last read;
+    units are flops for "gemm" and bytes for "rows" (s x A, s dy B^T) and "grad" (dA, dB)."""
+    n = len(PROFILE_KINDS)
+    ms, un, cnt = (ctypes.c_double * n)(), (ctypes.c_double * n)(), (ctypes.c_int * n)()
+    st = lib.mlora_profile_kernels_read(ms, un, cnt)
     if st != 0:
-        raise MloraError(st, "mlora_profile_gemm_read")
-    return ms.value, fl.value, n.value
+        raise MloraError(st, "mlora_profile_kernels_read")
+    return {k: (ms[i], un[i], cnt[i]) for i, k in enumerate(PROFILE_KINDS)}

@@ -470,11 +470,38 @@ int pick_row_tile(const SegTable& st) {
   return tm;
 }
 
+// Algorithmic bytes of one launch: the tasks' rows of the big operand read once, the outputs
+// written once, the small operands read once.
+template <int NP>
+double rows_bytes(const RowsArgs<NP>& a) {
+  const double rows = a.K > 0 ? a.off[a.K] - a.off[0] : 0;
+  double b = rows * a.inner * 2.0;
+  for (int p = 0; p < NP; ++p) {
+    b += rows * a.ldz[p] * 2.0;
+    for (int k = 0; k < a.K; ++k) b += (double)a.rank[p][k] * a.inner * 2.0;
+  }
+  return b;
+}
+
+template <int NP>
+double grad_bytes(const GradArgs<NP>& a) {
+  const double rows = a.K > 0 ? a.off[a.K] - a.off[0] : 0;
+  double b = rows * a.wide * 2.0;
+  for (int p = 0; p < NP; ++p) {
+    b += rows * a.ldz[p] * 2.0;
+    for (int k = 0; k < a.K; ++k) b += (double)a.rank[p][k] * a.wide * 4.0;
+  }
+  return b;
+}
+
 template <bool KMAJOR, int NQ, int TM, int NP>
 hipError_t launch_rows_one(const RowsArgs<NP>& a, int blocks, hipStream_t s) {
   if constexpr (NP * NQ <= 8) {
+    const int slot = profile_begin(kProfileRows, rows_bytes(a), s);
     hipLaunchKernelGGL((k_lowrank_mfma<KMAJOR, NQ, kRing, TM, NP>), dim3(blocks), dim3(TM * 2), 0, s, a);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    profile_end(slot, s);
+    return e;
   } else {
     return hipErrorInvalidValue;
   }
@@ -497,8 +524,11 @@ hipError_t launch_rows(const RowsArgs<NP>& a, int nq, int tm, int blocks, hipStr
 template <bool WIDE_FIRST, int NQ, int NP>
 hipError_t launch_grad_one(const GradArgs<NP>& a, int blocks, hipStream_t s) {
   if constexpr (NP * NQ <= 8) {
+    const int slot = profile_begin(kProfileGrad, grad_bytes(a), s);
     hipLaunchKernelGGL((k_grad_mfma<WIDE_FIRST, NQ, kRing, NP>), dim3(blocks), dim3(256), 0, s, a);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    profile_end(slot, s);
+    return e;
   } else {
     return hipErrorInvalidValue;
   }

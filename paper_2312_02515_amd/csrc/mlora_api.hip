@@ -242,7 +242,7 @@ mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* d
                             size_t workspace_bytes, void* hip_stream) {
   mlora_status st = validate(p);
   if (st != MLORA_OK) return st;
-  if (X == nullptr || dY == nullptr || saved == nullptr) return MLORA_ERR_NULL;
+  if (p->T > 0 && (X == nullptr || dY == nullptr || saved == nullptr)) return MLORA_ERR_NULL;
   st = check_grad_tables(p, dA, dB);
   if (st != MLORA_OK) return st;
   if (workspace == nullptr || workspace_bytes < mlora_lora_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
@@ -257,7 +257,7 @@ mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, con
                                       size_t workspace_bytes, void* hip_stream) {
   mlora_status st = validate(p);
   if (st != MLORA_OK) return st;
-  if (X == nullptr || dY == nullptr) return MLORA_ERR_NULL;
+  if (p->T > 0 && (X == nullptr || dY == nullptr)) return MLORA_ERR_NULL;
   st = check_grad_tables(p, dA, dB);
   if (st != MLORA_OK) return st;
   if (workspace == nullptr || workspace_bytes < mlora_lora_recompute_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
@@ -316,9 +316,12 @@ mlora_status mlora_lora_group_bwd(const mlora_problem* const* ps, int P, const v
                                   void* hip_stream) {
   mlora_status st = validate_group(ps, P);
   if (st != MLORA_OK) return st;
-  if (X == nullptr || dY == nullptr || saved == nullptr) return MLORA_ERR_NULL;
-  for (int p = 0; p < P; ++p)
-    if (dY[p] == nullptr || saved[p] == nullptr) return MLORA_ERR_NULL;
+  if (dY == nullptr || saved == nullptr) return MLORA_ERR_NULL;
+  if (ps[0]->T > 0) {
+    if (X == nullptr) return MLORA_ERR_NULL;
+    for (int p = 0; p < P; ++p)
+      if (dY[p] == nullptr || saved[p] == nullptr) return MLORA_ERR_NULL;
+  }
   if (ps[0]->K > 0) {
     if (dA == nullptr || dB == nullptr) return MLORA_ERR_NULL;
     for (int p = 0; p < P; ++p) {
@@ -396,10 +399,19 @@ int mlora_last_hip_error(void) { return g_last_hip_error; }
 
 int mlora_set_kernel_path(int path) { return g_kernel_path.exchange(path); }
 
-int mlora_profile_gemm(int enable) { return gemm_profile_enable(enable); }
+int mlora_profile_kernels(int enable) { return profile_enable(enable); }
 
-mlora_status mlora_profile_gemm_read(double* ms_total, double* flops_total, int* launches) {
-  return hip_status(gemm_profile_read(ms_total, flops_total, launches));
+mlora_status mlora_profile_kernels_read(double* ms_total, double* units_total, int* launches) {
+  double ms[kProfileKinds], un[kProfileKinds];
+  int n[kProfileKinds];
+  const hipError_t e = profile_read(ms, un, n);
+  if (e != hipSuccess) return hip_status(e);
+  for (int k = 0; k < kProfileKinds; ++k) {
+    if (ms_total) ms_total[k] = ms[k];
+    if (units_total) units_total[k] = un[k];
+    if (launches) launches[k] = n[k];
+  }
+  return MLORA_OK;
 }
 
 }  // extern "C"

@@ -97,8 +97,12 @@ struct GemmOperands {
 hipError_t gemm_mfma_sum_nt(int n, const GemmOperands* ops, bf16* C, int M, int N, const SegTable& st,
                             hipStream_t stream);
 
-int gemm_profile_enable(int enable);
-hipError_t gemm_profile_read(double* ms_total, double* flops_total, int* launches);
+// profile.hip : optional HIP-event timing of the MFMA kernels' launches, by kind
+enum { kProfileGemm = 0, kProfileRows = 1, kProfileGrad = 2, kProfileKinds = 3 };
+int profile_enable(int enable);
+int profile_begin(int kind, double units, hipStream_t stream);
+void profile_end(int slot, hipStream_t stream);
+hipError_t profile_read(double* ms, double* units, int* launches);
 
 // lowrank_mfma.hip : bf16 MFMA kernels for Z, G (row-local) and dA_k, dB_k (reduce over a task's tokens)
 hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* Out, const PtrTable& M, bool a_major);

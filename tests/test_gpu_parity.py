@@ -116,6 +116,41 @@ def test_isolation_on_gpu():
     assert not torch.equal(a["Y"][256:512], b["Y"][256:512])
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_max_adapters(dtype):
+    """64 tasks (the library's maximum) of 3..66 tokens with ranks cycling through 8, 16, 24, 32:
+    the whole kernel-argument tables are in use."""
+    K = 64
+    tokens = [3 + k for k in range(K)]
+    ranks = [8 * (1 + k % 4) for k in range(K)]
+    T = sum(tokens) + 9
+    inp = _inputs(T, 128, 192, tokens, ranks, dtype, lead=4, seed=31, scal=[0.5 + 0.05 * k for k in range(K)])
+    out = run_hip(inp)
+    check_full(inp, out, TOL[dtype], label="64 adapters")
+
+
+def test_empty_batch_on_gpu():
+    """T = 0: both calls return without touching anything; overwrite mode zeroes dA_k, dB_k."""
+    from paper_2312_02515_amd import binding as mb
+    W = torch.randn(64, 64, device=DEV).to(torch.bfloat16)
+    A = [torch.randn(64, 8, device=DEV).to(torch.bfloat16)]
+    B = [torch.randn(8, 64, device=DEV).to(torch.bfloat16)]
+    prob = mb.Problem(0, 64, 64, W, [0, 0], [8], [2.0], A, B)
+    X = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
+    Y = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
+    saved, ws = prob.alloc_saved(), prob.alloc_workspace()
+    dA, dB = prob.alloc_grads()
+    dA[0].fill_(3.0)
+    dB[0].fill_(4.0)
+    mb.mlora_lora_fwd(prob, X, Y, saved, ws)
+    mb.mlora_lora_bwd(prob, X, Y, saved, None, dA, dB, True, ws)
+    torch.cuda.synchronize()
+    assert (dA[0] == 3.0).all() and (dB[0] == 4.0).all()
+    mb.mlora_lora_bwd(prob, X, Y, saved, None, dA, dB, False, ws)
+    torch.cuda.synchronize()
+    assert not dA[0].any() and not dB[0].any()
+
+
 def _same_bits(a, b, K):
     assert torch.equal(a["Y"], b["Y"]) and torch.equal(a["dX"], b["dX"])
     for k in range(K):
