@@ -51,7 +51,8 @@ extern "C" {
 typedef enum {
   MLORA_OK            = 0,
   MLORA_ERR_NULL      = 1,  /* a required pointer is NULL                                   */
-  MLORA_ERR_SHAPE     = 2,  /* T, h or d negative, h or d zero, K out of range, sizes too big */
+  MLORA_ERR_SHAPE     = 2,  /* T, h or d negative, h or d zero, K out of range, sizes too big
+                              (T >= 2^31 - 1024, h or d > 2^22, 2^31 or more 256 x 256 tiles) */
   MLORA_ERR_SEGMENTS  = 3,  /* seg_offsets not monotone or outside [0, T]                   */
   MLORA_ERR_RANK      = 4,  /* a rank outside [1, MLORA_MAX_RANK]                           */
   MLORA_ERR_DTYPE     = 5,  /* dtype is not one of mlora_dtype                              */

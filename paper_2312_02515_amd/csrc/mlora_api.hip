@@ -14,8 +14,13 @@ mlora_status validate(const mlora_problem* p) {
   if (p == nullptr) return MLORA_ERR_NULL;
   if (p->dtype != MLORA_BF16 && p->dtype != MLORA_F32) return MLORA_ERR_DTYPE;
   if (p->T < 0 || p->h <= 0 || p->d <= 0) return MLORA_ERR_SHAPE;
-  // row indices and feature indices are 32-bit inside the kernels
-  if (p->T > 0x7fffffffLL - 1024 || p->h > (1 << 24) || p->d > (1 << 24)) return MLORA_ERR_SHAPE;
+  // row and feature indices are 32-bit inside the kernels, byte offsets within a 256-row tile
+  // too (256 rows x 4 Mi features x 2 B = 2^31), and a grid holds fewer than 2^31 tiles
+  if (p->T > 0x7fffffffLL - 1024 || p->h > (1 << 22) || p->d > (1 << 22)) return MLORA_ERR_SHAPE;
+  {
+    const int64_t wide = p->h > p->d ? p->h : p->d;
+    if ((p->T / 256 + 1) * (wide / 256 + 1) > 0x7fffffffLL) return MLORA_ERR_SHAPE;
+  }
   if (p->K < 0 || p->K > kMaxK) return MLORA_ERR_SHAPE;
   if (p->W == nullptr) return MLORA_ERR_NULL;
   if (p->K > 0) {

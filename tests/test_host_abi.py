@@ -66,6 +66,9 @@ def test_valid_problem_sizes(mb):
     (dict(ranks=(8, 129)), 4),
     (dict(h=0), 2),
     (dict(T=-1), 2),
+    (dict(d=(1 << 22) + 64), 2),           # feature sizes beyond 4 Mi
+    (dict(T=1 << 31, off=(0, 32, 64)), 2),  # too many rows
+    (dict(T=(1 << 31) - 2048, d=1 << 22, off=(0, 32, 64)), 2),  # more than 2^31 tiles
     (dict(null_A=True), 1),
 ])
 def test_validation_codes(mb, kw, code):
