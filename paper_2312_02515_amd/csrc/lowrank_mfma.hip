@@ -242,6 +242,182 @@ __global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const RowsArgs<NP> ra) 
 }
 
 // ------------------------------------------------------------------------------------------
+// The same product for calls with few rows (the 32-row tiling still leaves the chip short of
+// waves): a block owns 32 rows and its 4 waves split the contraction -- wave w takes the tiles
+// kt = w, w + 4, ... through a ring of its own (no barrier in the loop: a wave reads only what
+// its own loads wrote), then waves 1..3 hand their partial sums to wave 0 through LDS, which adds
+// them in that order (deterministic) and writes the rows.  Ranks up to 64.
+// ------------------------------------------------------------------------------------------
+template <bool SMALL_KMAJOR, int NQ, int NS>
+__global__ __launch_bounds__(256) void k_lowrank_mfma_splitk(const RowsArgs<1> ra) {
+  constexpr int TM = 32, NSPLIT = 4;
+  constexpr int SBYTES = NQ * 32 * 128;
+  constexpr int SREG = SBYTES + 1024;
+  constexpr int XB = TM * 128;
+  static_assert(NQ <= 2, "LDS holds four rings only up to rank 64");
+  __shared__ __attribute__((aligned(1024))) char sXall[NSPLIT * NS * XB];
+  __shared__ __attribute__((aligned(1024))) char sSall[NSPLIT * NS * SREG];
+  static_assert(3 * NQ * 16 * 256 <= NSPLIT * NS * SREG, "partial sums fit the small-operand rings");
+
+  const bf16* __restrict__ In = ra.In;
+  const int inner = ra.inner;
+  int b = blockIdx.x, k = 0;
+  for (; k < ra.K; ++k) {
+    const int nb = (ra.off[k + 1] - ra.off[k] + TM - 1) / TM;
+    if (b < nb) break;
+    b -= nb;
+  }
+  if (k >= ra.K) return;
+  const int lo = ra.off[k] + b * TM;
+  const int hi = (ra.off[k + 1] < lo + TM) ? ra.off[k + 1] : lo + TM;
+  const int r = ra.rank[0][k];
+  const bf16* Mk = static_cast<const bf16*>(ra.M[0].p[k]);
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  char* const sXw = sXall + wave * NS * XB;
+  char* const sSw = sSall + wave * NS * SREG;
+  if (lane < 16) {
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) reinterpret_cast<int*>(sSw + s_ * SREG + SBYTES)[lane] = 0;
+  }
+
+  const bf16* xptr[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int rl = 8 * it + (lane >> 3);
+    const int c = (lane & 7) ^ ((rl >> 1) & 7);
+    int row = lo + rl;
+    row = row < hi ? row : hi - 1;
+    xptr[it] = In + (size_t)row * inner + c * 8;
+  }
+  const int pieces = r / 8;
+  const bf16* sptr[4 * NQ];
+#pragma unroll
+  for (int it = 0; it < 4 * NQ; ++it) {
+    const int piece = it < pieces ? it : 0;
+    if (SMALL_KMAJOR) {
+      sptr[it] = Mk + piece * 512 + lane * 8;
+    } else {
+      int q = 8 * piece + (lane >> 3);
+      const int c = (lane & 7) ^ ((q >> 1) & 7);
+      q = q < r ? q : r - 1;
+      sptr[it] = Mk + (size_t)q * inner + c * 8;
+    }
+  }
+  const size_t sstep = SMALL_KMAJOR ? (size_t)64 * r : (size_t)64;
+  constexpr int PER_TILE = 4 + 4 * NQ;
+
+  auto issue = [&](int kt, int stage) {
+    char* sx = sXw + stage * XB;
+    char* ss = sSw + stage * SREG;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) load_lds_16B(xptr[it] + (size_t)kt * 64, sx + it * 1024);
+#pragma unroll
+    for (int it = 0; it < 4 * NQ; ++it) load_lds_16B(sptr[it] + (size_t)kt * sstep, ss + it * 1024);
+  };
+
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int fsw = (l32 >> 1) & 7;
+  const int L16 = lane & 15, blk = lane >> 4, kq = L16 >> 2;
+  const int tr_k = 8 * (blk >> 1) + kq;
+  const int tr_n = 16 * (blk & 1) + 4 * (L16 & 3);
+
+  f32x16 acc[NQ];
+#pragma unroll
+  for (int j = 0; j < NQ; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+  auto compute = [&](int stage) {
+    const char* sx = sXw + stage * XB;
+    const char* ss = sSw + stage * SREG;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int coff = ((2 * ks + lhi) ^ fsw) << 4;
+      const bf16x8 xf = *(const bf16x8*)(sx + l32 * 128 + coff);
+#pragma unroll
+      for (int j = 0; j < NQ; ++j) {
+        if (32 * j < r) {
+          bf16x8 sf;
+          if (SMALL_KMAJOR) {
+            const int n = 32 * j + tr_n;
+            const int kk = 16 * ks + tr_k;
+            const char* p0 = ss + ((n < r) ? (kk * r + n) * 2 : SBYTES);
+            const char* p1 = ss + ((n < r) ? ((kk + 4) * r + n) * 2 : SBYTES);
+            sf = join(lds_read_tr(p0), lds_read_tr(p1));
+          } else {
+            sf = *(const bf16x8*)(ss + (32 * j + l32) * 128 + coff);
+          }
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, xf, acc[j], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  // this wave's tiles: kt = wave + 4 i, i < n
+  const int KT = inner / 64;
+  const int n = (KT - wave + NSPLIT - 1) / NSPLIT;
+#pragma unroll
+  for (int s_ = 0; s_ < NS - 1; ++s_)
+    if (s_ < n) issue(wave + NSPLIT * s_, s_);
+  for (int i0 = 0; i0 < n; i0 += NS) {
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) {
+      const int i = i0 + s_;
+      if (i < n) {
+        if (i + NS - 2 < n)
+          wait_vmcnt<(NS - 2) * PER_TILE>();
+        else
+          wait_vmcnt<0>();
+        // the stage of tile i-1 is refilled: its fragment reads have returned
+        wait_lds();
+        if (i + NS - 1 < n) issue(wave + NSPLIT * (i + NS - 1), (s_ + NS - 1) % NS);
+        compute(s_);
+      }
+    }
+  }
+
+  // partial sums of waves 1..3 -> LDS (the rings are idle after the barrier), wave 0 adds them
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(sSall);
+  if (wave > 0) {
+#pragma unroll
+    for (int j = 0; j < NQ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) red[(((wave - 1) * NQ + j) * 16 + e) * 64 + lane] = acc[j][e];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+#pragma unroll
+  for (int w = 0; w < NSPLIT - 1; ++w)
+#pragma unroll
+    for (int j = 0; j < NQ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][e] += red[((w * NQ + j) * 16 + e) * 64 + lane];
+
+  const float s = ra.s[0][k];
+  const int ldz = ra.ldz[0];
+  bf16* __restrict__ Out = ra.Out[0];
+  const int row = lo + l32;
+  if (row < hi) {
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int q = 32 * j + 8 * g + 4 * lhi;
+        if (q < ldz) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16>((q + e < r) ? acc[j][4 * g + e] * s : 0.f);
+          *(bf16x4*)(Out + (size_t)row * ldz + q) = o;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Gradient products whose contraction runs over the tokens of one task:
 //   WIDE_FIRST = true : out_pk[c, q] (+)= sum_t Big[t, c] * Small_p[t, q]   (dA_k = x_k^T G,  out row stride r_k)
 //   WIDE_FIRST = false: out_k[q, j]  (+)= sum_t Small[t, q] * Big[t, j]     (dB_k = Z^T dy_k, out row stride wide)
@@ -514,8 +690,23 @@ hipError_t launch_rows_tm(const RowsArgs<NP>& a, int tm, int blocks, hipStream_t
   return launch_rows_one<KMAJOR, NQ, 32, NP>(a, blocks, s);
 }
 
+template <bool KMAJOR, int NQ>
+hipError_t launch_rows_splitk(const RowsArgs<1>& a, int blocks, hipStream_t s) {
+  const int slot = profile_begin(kProfileRows, rows_bytes(a), s);
+  hipLaunchKernelGGL((k_lowrank_mfma_splitk<KMAJOR, NQ, kRing>), dim3(blocks), dim3(256), 0, s, a);
+  const hipError_t e = hipGetLastError();
+  profile_end(slot, s);
+  return e;
+}
+
 template <bool KMAJOR, int NP>
 hipError_t launch_rows(const RowsArgs<NP>& a, int nq, int tm, int blocks, hipStream_t s) {
+  if constexpr (NP == 1) {
+    // few rows: four waves per 32-row block, each on a quarter of the contraction
+    if (tm == 32 && nq <= 2 && a.inner >= 1024 && blocks <= 1024) {
+      return nq == 1 ? launch_rows_splitk<KMAJOR, 1>(a, blocks, s) : launch_rows_splitk<KMAJOR, 2>(a, blocks, s);
+    }
+  }
   if (nq == 1) return launch_rows_tm<KMAJOR, 1, NP>(a, tm, blocks, s);
   if (nq == 2) return launch_rows_tm<KMAJOR, 2, NP>(a, tm, blocks, s);
   return launch_rows_tm<KMAJOR, 4, NP>(a, tm, blocks, s);
