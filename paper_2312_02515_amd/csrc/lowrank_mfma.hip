@@ -21,6 +21,23 @@ namespace {
 
 using namespace stage;
 
+// Bank-conflict swizzle of a small tile stored with the contraction index as its rows
+// ([64 k][w] bf16) and read with transposing LDS reads, which touch 4 consecutive rows x 64 B per
+// 16 lanes: with rows of 128 or 256 B those rows would share banks, so the 64-byte segments of
+// row k are permuted by XOR with seg_swizzle(k, w).  A direct-to-LDS load fills LDS contiguously,
+// so the permutation is applied by choosing which global chunk each lane fetches, and undone in
+// the read address (column n -> n ^ (seg_swizzle << 5)).
+__device__ __forceinline__ int seg_swizzle(int k, int w) {
+  return w == 128 ? (k & 3) : (w == 64 ? ((k >> 1) & 1) : 0);
+}
+// element offset inside the tile that LDS chunk position `chunk` (16 B units) must be filled with
+__device__ __forceinline__ int swizzled_source(int chunk, int w) {
+  const int cpr = w / 8;
+  const int row = chunk / cpr, pc = chunk % cpr;
+  const int seg = (pc >> 2) ^ seg_swizzle(row, w);
+  return row * w + (((seg << 2) | (pc & 3)) << 3);
+}
+
 
 // ------------------------------------------------------------------------------------------
 // Arguments of the two kernels, passed by value.  NP > 1 serves projections that share their
@@ -124,7 +141,7 @@ __global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const RowsArgs<NP> ra) 
       // that every wave issues the same number of loads per tile
       const int piece = (wave + NWV * it) < pieces ? (wave + NWV * it) : 0;
       if (SMALL_KMAJOR) {
-        sptr[p][it] = Mk + piece * 512 + lane * 8;
+        sptr[p][it] = Mk + swizzled_source(piece * 64 + lane, r[p]);
       } else {
         int q = 8 * piece + (lane >> 3);
         const int c = (lane & 7) ^ ((q >> 1) & 7);
@@ -178,8 +195,9 @@ __global__ __launch_bounds__(TM * 2) void k_lowrank_mfma(const RowsArgs<NP> ra) 
             if (SMALL_KMAJOR) {
               const int n = 32 * j + tr_n;
               const int kk = 16 * ks + tr_k;
-              const char* p0 = ss + ((n < r[p]) ? (kk * r[p] + n) * 2 : SBYTES);
-              const char* p1 = ss + ((n < r[p]) ? ((kk + 4) * r[p] + n) * 2 : SBYTES);
+              const int ns = n ^ (seg_swizzle(kk, r[p]) << 5);
+              const char* p0 = ss + ((n < r[p]) ? (kk * r[p] + ns) * 2 : SBYTES);
+              const char* p1 = ss + ((n < r[p]) ? ((kk + 4) * r[p] + ns) * 2 : SBYTES);
               sf = join(lds_read_tr(p0), lds_read_tr(p1));
             } else {
               sf = *(const bf16x8*)(ss + (32 * j + l32) * 128 + coff);
@@ -297,7 +315,7 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma_splitk(const RowsArgs<1> r
   for (int it = 0; it < 4 * NQ; ++it) {
     const int piece = it < pieces ? it : 0;
     if (SMALL_KMAJOR) {
-      sptr[it] = Mk + piece * 512 + lane * 8;
+      sptr[it] = Mk + swizzled_source(piece * 64 + lane, r);
     } else {
       int q = 8 * piece + (lane >> 3);
       const int c = (lane & 7) ^ ((q >> 1) & 7);
@@ -343,8 +361,9 @@ __global__ __launch_bounds__(256) void k_lowrank_mfma_splitk(const RowsArgs<1> r
           if (SMALL_KMAJOR) {
             const int n = 32 * j + tr_n;
             const int kk = 16 * ks + tr_k;
-            const char* p0 = ss + ((n < r) ? (kk * r + n) * 2 : SBYTES);
-            const char* p1 = ss + ((n < r) ? ((kk + 4) * r + n) * 2 : SBYTES);
+            const int ns = n ^ (seg_swizzle(kk, r) << 5);
+            const char* p0 = ss + ((n < r) ? (kk * r + ns) * 2 : SBYTES);
+            const char* p1 = ss + ((n < r) ? ((kk + 4) * r + ns) * 2 : SBYTES);
             sf = join(lds_read_tr(p0), lds_read_tr(p1));
           } else {
             sf = *(const bf16x8*)(ss + (32 * j + l32) * 128 + coff);
@@ -482,9 +501,9 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const GradArgs<NP> ga) {
       // pieces beyond the tile re-fetch piece 0 into their own (never read) slot, so that every
       // wave issues the same number of loads per tile
       const int piece = (wave + 4 * it) < cpr ? (wave + 4 * it) : 0;
-      const int chunk = piece * 64 + lane;
-      srow[p][it] = chunk / cpr;
-      scol[p][it] = (chunk % cpr) * 8;
+      const int src = swizzled_source(piece * 64 + lane, ldz[p]);
+      srow[p][it] = src / ldz[p];
+      scol[p][it] = src % ldz[p];
     }
   }
   constexpr int PER_TILE = 4 + NP * NQ;
@@ -536,8 +555,9 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const GradArgs<NP> ga) {
         for (int j = 0; j < NQ; ++j) {
           if (32 * j < ldz[p]) {
             const int n = 32 * j + tr_n;
-            const char* p0 = ss + ((n < ldz[p]) ? (kk * ldz[p] + n) * 2 : SBYTES);
-            const char* p1 = ss + ((n < ldz[p]) ? ((kk + 4) * ldz[p] + n) * 2 : SBYTES);
+            const int ns = n ^ (seg_swizzle(kk, ldz[p]) << 5);
+            const char* p0 = ss + ((n < ldz[p]) ? (kk * ldz[p] + ns) * 2 : SBYTES);
+            const char* p1 = ss + ((n < ldz[p]) ? ((kk + 4) * ldz[p] + ns) * 2 : SBYTES);
             short4v s0 = lds_read_tr(p0), s1 = lds_read_tr(p1);
             if (valid < 64) {
               // the lane's 8 contraction indices are tokens 16ks + 8*lhi + 0..7 of the tile
