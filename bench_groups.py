@@ -9,8 +9,8 @@ bench.py's workload (T = 32768, 16 adapters of ranks {8,16,32,64}).
             dX = sum_p dX_p with elementwise adds (what an autograd engine does with the
             single-projection operator)
 
-Prints one JSON line per group with the median time of each mode.  Not part of bench.py's
-contract; the numbers are quoted in the design doc.
+Prints one JSON line per group with the median time of each mode.  A side experiment:
+bench.py is the benchmark proper.
 """
 import argparse
 import json

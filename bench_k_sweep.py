@@ -9,7 +9,7 @@ section 4.4): fixed total tokens T, K = 1 ... 64 adapters of equal share, rank 1
 
 Both run through the same kernels of this library on one stream, inputs resident in HBM.
 Prints one JSON line per (T, K) with the median time of each mode over `--iters` repetitions
-and their ratio.  Not part of bench.py's contract; the numbers are quoted in the design doc.
+and their ratio.  A side experiment: bench.py is the benchmark proper.
 """
 import argparse
 import json
