@@ -68,6 +68,11 @@ struct GradArgs {
   unsigned char rank[NP][kMaxK];
   OutTable out[NP];
   int accumulate, chunks;
+  // splits > 1 (NP == 1 only): a task's tokens are cut into `splits` ranges, one block each;
+  // block (task k, range s) overwrites its partial sums at part + (s * rtotal + rbase_k) * wide
+  // (same element order as the output), and k_grad_reduce adds the ranges in order
+  int splits, rtotal;
+  float* part;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -465,9 +470,17 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const GradArgs<NP> ga) {
 
   const bf16* __restrict__ Big = ga.Big;
   const int wide = ga.wide, T = ga.T;
-  const int k = blockIdx.x / ga.chunks, ch = blockIdx.x % ga.chunks;
+  const int ch = blockIdx.x % ga.chunks;
+  const int sp = (blockIdx.x / ga.chunks) % ga.splits;
+  const int k = blockIdx.x / (ga.chunks * ga.splits);
   const int col0 = ch * WC;
-  const int lo = ga.off[k], hi = ga.off[k + 1];
+  int lo = ga.off[k], hi = ga.off[k + 1];
+  if (ga.splits > 1) {
+    // token range of this block: whole 64-token tiles, possibly empty (then zeros are written)
+    const int len = ((hi - lo + ga.splits - 1) / ga.splits + 63) / 64 * 64;
+    lo = lo + sp * len < hi ? lo + sp * len : hi;
+    hi = lo + len < hi ? lo + len : hi;
+  }
   const int tk = hi - lo;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -601,11 +614,17 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const GradArgs<NP> ga) {
     }
   }
 
-  const int accumulate = ga.accumulate;
+  int accumulate = ga.accumulate;
 #pragma unroll
   for (int p = 0; p < NP; ++p) {
     float* o = ga.out[p].p[k];
     const int r = ga.rank[p][k];
+    if (NP == 1 && ga.splits > 1) {
+      int rbase = 0;
+      for (int kk = 0; kk < k; ++kk) rbase += ga.rank[0][kk];
+      o = ga.part + ((size_t)sp * ga.rtotal + rbase) * wide;
+      accumulate = 0;
+    }
     if (WIDE_FIRST) {
       // D[i = column c of Big][j = q]: lane holds q = 32j + l32 and c = col0 + 32*wave + 8g + 4*lhi + e
 #pragma unroll
@@ -643,6 +662,32 @@ __global__ __launch_bounds__(256) void k_grad_mfma(const GradArgs<NP> ga) {
       }
     }
   }
+}
+
+// Adds the token ranges' partial sums of k_grad_mfma in range order (deterministic) into the
+// tasks' outputs.  One thread per output element; `total` = rtotal * wide elements.
+struct ReduceArgs {
+  const float* part;
+  int splits, rtotal, wide, K, accumulate;
+  unsigned char rank[kMaxK];
+  OutTable out;
+};
+__global__ __launch_bounds__(256) void k_grad_reduce(const ReduceArgs a) {
+  const size_t total = (size_t)a.rtotal * a.wide;
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= total) return;
+  float sum = 0.f;
+  for (int s_ = 0; s_ < a.splits; ++s_) sum += a.part[(size_t)s_ * total + g];
+  // which task: element g lies in [rbase_k * wide, (rbase_k + r_k) * wide)
+  size_t base = 0;
+  int k = 0;
+  for (; k < a.K; ++k) {
+    const size_t n = (size_t)a.rank[k] * a.wide;
+    if (g < base + n) break;
+    base += n;
+  }
+  float* dst = a.out.p[k] + (g - base);
+  *dst = a.accumulate ? *dst + sum : sum;
 }
 
 // Ring depth: three stages (two tiles in flight) keep a block at 75 KiB of LDS for ranks up to 64,
@@ -791,6 +836,9 @@ hipError_t grad_group(const LowrankGroupItem* it, const SegTable& st, const bf16
   }
   a.accumulate = accumulate;
   a.chunks = (wide + 127) / 128;
+  a.splits = 1;
+  a.rtotal = 0;
+  a.part = nullptr;
   return launch_grad<true, NP>(a, nq, st.K * a.chunks, s);
 }
 
@@ -819,8 +867,30 @@ hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* 
 }
 
 // dA_k = x_k^T G (wide_first = true; Big = X [T,h], Small = G) or dB_k = Z^T dy_k (Big = dY [T,d], Small = Z).
+// Token ranges per task for the gradient kernels: 1 when tasks x column blocks fill the chip,
+// otherwise enough ranges for about two blocks per CU (at most 16, at least 256 tokens each).
+int grad_splits(const SegTable& st, int wide) {
+  const int blocks = st.K * ((wide + 127) / 128);
+  if (st.K == 0 || blocks >= 384) return 1;
+  int longest = 0;
+  for (int k = 0; k < st.K; ++k) longest = st.off[k + 1] - st.off[k] > longest ? st.off[k + 1] - st.off[k] : longest;
+  int s = (512 + blocks - 1) / blocks;
+  s = s < 16 ? s : 16;
+  s = s < longest / 256 ? s : longest / 256;
+  return s > 1 ? s : 1;
+}
+
+// Bytes of partial sums grad_mfma needs for an output of `wide` columns (0 when it does not split).
+size_t grad_partial_bytes(const SegTable& st, int wide) {
+  const int s = grad_splits(st, wide);
+  if (s <= 1) return 0;
+  size_t rtotal = 0;
+  for (int k = 0; k < st.K; ++k) rtotal += st.rank[k];
+  return align_up((size_t)s * rtotal * wide * sizeof(float), 256);
+}
+
 hipError_t grad_mfma(const CallCtx& c, const bf16* Big, int wide, const bf16* Small, const OutTable& out,
-                     int accumulate, bool wide_first) {
+                     int accumulate, bool wide_first, float* partial) {
   if (c.K == 0) return hipSuccess;
   GradArgs<1> a;
   a.Big = Big;
@@ -834,9 +904,27 @@ hipError_t grad_mfma(const CallCtx& c, const bf16* Big, int wide, const bf16* Sm
   a.out[0] = out;
   a.accumulate = accumulate;
   a.chunks = (wide + 127) / 128;
+  a.splits = partial != nullptr ? grad_splits(c.st, wide) : 1;
+  a.rtotal = 0;
+  for (int k = 0; k < c.K; ++k) a.rtotal += c.st.rank[k];
+  a.part = partial;
   const int nq = nq_of(c.ldz);
-  const int blocks = c.K * a.chunks;
-  return wide_first ? launch_grad<true, 1>(a, nq, blocks, c.stream) : launch_grad<false, 1>(a, nq, blocks, c.stream);
+  const int blocks = c.K * a.chunks * a.splits;
+  hipError_t e =
+      wide_first ? launch_grad<true, 1>(a, nq, blocks, c.stream) : launch_grad<false, 1>(a, nq, blocks, c.stream);
+  if (e != hipSuccess || a.splits == 1) return e;
+  ReduceArgs r;
+  r.part = partial;
+  r.splits = a.splits;
+  r.rtotal = a.rtotal;
+  r.wide = wide;
+  r.K = c.K;
+  r.accumulate = accumulate;
+  for (int k = 0; k < kMaxK; ++k) r.rank[k] = (unsigned char)c.st.rank[k];
+  r.out = out;
+  const size_t total = (size_t)a.rtotal * wide;
+  hipLaunchKernelGGL(k_grad_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c.stream, r);
+  return hipGetLastError();
 }
 
 // Whether np projections whose widest low-rank row stride is max_ldz fit the shared-input kernels

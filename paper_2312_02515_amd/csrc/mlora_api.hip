@@ -89,6 +89,15 @@ bool mfma_shapes_ok(const mlora_problem* p) {
 bool mfma_gemm_applies(const mlora_problem* p) { return !(g_kernel_path.load() & 1) && mfma_shapes_ok(p); }
 bool mfma_lowrank_applies(const mlora_problem* p) { return !(g_kernel_path.load() & 2) && mfma_shapes_ok(p); }
 
+// Scratch for the token-split form of the gradient kernels (0 when they do not split)
+size_t grad_scratch_bytes(const mlora_problem* p) {
+  if (!mfma_shapes_ok(p) || p->K == 0) return 0;
+  CallCtx c;
+  fill_ctx(p, nullptr, &c);
+  const size_t a = grad_partial_bytes(c.st, c.h), b = grad_partial_bytes(c.st, c.d);
+  return a > b ? a : b;
+}
+
 mlora_status hip_status(hipError_t e) {
   if (e == hipSuccess) return MLORA_OK;
   g_last_hip_error = (int)e;
@@ -128,7 +137,8 @@ mlora_status check_grad_tables(const mlora_problem* p, float* const* dA, float* 
 // G, dB_k and dA_k, given Z
 // (with `skip_dA` the caller computes dA_k itself from G)
 hipError_t adapter_grads_impl(const mlora_problem* p, const CallCtx& c, const void* X, const void* dY, const void* Z,
-                              void* G, float* const* dA, float* const* dB, int accumulate, bool skip_dA = false) {
+                              void* G, float* const* dA, float* const* dB, int accumulate, float* partial,
+                              bool skip_dA = false) {
   OutTable ta, tb;
   for (int k = 0; k < kMaxK; ++k) {
     ta.p[k] = k < p->K ? dA[k] : nullptr;
@@ -137,8 +147,9 @@ hipError_t adapter_grads_impl(const mlora_problem* p, const CallCtx& c, const vo
   hipError_t e;
   if (mfma_lowrank_applies(p) && aligned16(X) && aligned16(dY) && aligned16(Z) && aligned16(G)) {
     e = lowrank_rows_mfma(c, (const bf16*)dY, c.d, (bf16*)G, c.B, false);
-    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)dY, c.d, (const bf16*)Z, tb, accumulate ? 1 : 0, false);
-    if (e == hipSuccess && !skip_dA) e = grad_mfma(c, (const bf16*)X, c.h, (const bf16*)G, ta, accumulate ? 1 : 0, true);
+    if (e == hipSuccess) e = grad_mfma(c, (const bf16*)dY, c.d, (const bf16*)Z, tb, accumulate ? 1 : 0, false, partial);
+    if (e == hipSuccess && !skip_dA)
+      e = grad_mfma(c, (const bf16*)X, c.h, (const bf16*)G, ta, accumulate ? 1 : 0, true, partial);
   } else {
     e = generic_G(c, dY, G);
     if (e == hipSuccess) e = generic_dB(c, Z, dY, tb, accumulate ? 1 : 0);
@@ -149,8 +160,8 @@ hipError_t adapter_grads_impl(const mlora_problem* p, const CallCtx& c, const vo
 
 // G, dB_k, dA_k and (unless dX is NULL) dX, given Z
 hipError_t backward_impl(const mlora_problem* p, const CallCtx& c, const void* X, const void* dY, const void* Z, void* G,
-                         void* dX, float* const* dA, float* const* dB, int accumulate) {
-  hipError_t e = adapter_grads_impl(p, c, X, dY, Z, G, dA, dB, accumulate);
+                         void* dX, float* const* dA, float* const* dB, int accumulate, float* partial) {
+  hipError_t e = adapter_grads_impl(p, c, X, dY, Z, G, dA, dB, accumulate, partial);
   if (e == hipSuccess && dX != nullptr && p->T > 0) {
     if (mfma_gemm_applies(p) && aligned16(dY) && aligned16(dX) && aligned16(G))
       e = gemm_mfma((const bf16*)dY, (const bf16*)p->W, (bf16*)dX, c.T, c.h, c.d, false, (const bf16*)G, c.ldz, c.st, c.A,
@@ -207,13 +218,13 @@ size_t mlora_lora_saved_bytes(const mlora_problem* p) {
 
 size_t mlora_lora_workspace_bytes(const mlora_problem* p) {
   if (validate(p) != MLORA_OK) return 0;
-  size_t b = lowrank_bytes(p);  // G
+  size_t b = lowrank_bytes(p) + grad_scratch_bytes(p);  // G, partial sums of split gradient launches
   return b ? b : 256;
 }
 
 size_t mlora_lora_recompute_workspace_bytes(const mlora_problem* p) {
   if (validate(p) != MLORA_OK) return 0;
-  size_t b = 2 * lowrank_bytes(p);  // G, then Z
+  size_t b = 2 * lowrank_bytes(p) + grad_scratch_bytes(p);  // G, Z, partial sums
   return b ? b : 256;
 }
 
@@ -254,7 +265,8 @@ mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* d
   if (p->T == 0 && accumulate) return MLORA_OK;
   CallCtx c;
   fill_ctx(p, hip_stream, &c);
-  return hip_status(backward_impl(p, c, X, dY, saved, workspace, dX, dA, dB, accumulate));
+  float* partial = grad_scratch_bytes(p) ? reinterpret_cast<float*>(static_cast<char*>(workspace) + lowrank_bytes(p)) : nullptr;
+  return hip_status(backward_impl(p, c, X, dY, saved, workspace, dX, dA, dB, accumulate, partial));
 }
 
 mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, const void* dY, void* dX,
@@ -272,7 +284,9 @@ mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, con
   void* Z = static_cast<char*>(workspace) + lowrank_bytes(p);
   hipError_t e = p->T > 0 ? compute_Z(p, c, X, Z) : hipSuccess;
   if (e != hipSuccess) return hip_status(e);
-  return hip_status(backward_impl(p, c, X, dY, Z, workspace, dX, dA, dB, accumulate));
+  float* partial =
+      grad_scratch_bytes(p) ? reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * lowrank_bytes(p)) : nullptr;
+  return hip_status(backward_impl(p, c, X, dY, Z, workspace, dX, dA, dB, accumulate, partial));
 }
 
 mlora_status mlora_lora_group_validate(const mlora_problem* const* ps, int P) { return validate_group(ps, P); }
@@ -280,7 +294,13 @@ mlora_status mlora_lora_group_validate(const mlora_problem* const* ps, int P) { 
 size_t mlora_lora_group_workspace_bytes(const mlora_problem* const* ps, int P) {
   if (validate_group(ps, P) != MLORA_OK) return 0;
   size_t b = 0;
-  for (int p = 0; p < P; ++p) b += lowrank_bytes(ps[p]);  // every G_p is live until dX is written
+  size_t scratch = 0;
+  for (int p = 0; p < P; ++p) {
+    b += lowrank_bytes(ps[p]);  // every G_p is live until dX is written
+    const size_t g = grad_scratch_bytes(ps[p]);
+    scratch = g > scratch ? g : scratch;  // shared: the projections' gradient launches run in turn
+  }
+  b += scratch;
   return b ? b : 256;
 }
 
@@ -350,8 +370,9 @@ mlora_status mlora_lora_group_bwd(const mlora_problem* const* ps, int P, const v
   bool fused = ps[0]->K > 0 && group_lowrank_applies(ps, P, X);
   for (int p = 0; p < P; ++p) fused = fused && aligned16(dY[p]) && aligned16(saved[p]) && aligned16(G[p]);
   for (int p = 0; p < P; ++p) {
+    float* partial = grad_scratch_bytes(ps[p]) ? reinterpret_cast<float*>(w) : nullptr;  // behind the last G_p
     hipError_t e = adapter_grads_impl(ps[p], c[p], X, dY[p], saved[p], G[p], ps[0]->K > 0 ? dA[p] : nullptr,
-                                      ps[0]->K > 0 ? dB[p] : nullptr, accumulate, fused);
+                                      ps[0]->K > 0 ? dB[p] : nullptr, accumulate, partial, fused);
     if (e != hipSuccess) return hip_status(e);
   }
   if (fused) {

@@ -106,8 +106,12 @@ hipError_t profile_read(double* ms, double* units, int* launches);
 
 // lowrank_mfma.hip : bf16 MFMA kernels for Z, G (row-local) and dA_k, dB_k (reduce over a task's tokens)
 hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* Out, const PtrTable& M, bool a_major);
+// `partial`: grad_partial_bytes(c.st, wide) bytes of scratch for calls whose tasks x column blocks
+// do not fill the chip (the tokens of a task are then split over blocks); NULL = never split.
+int grad_splits(const SegTable& st, int wide);
+size_t grad_partial_bytes(const SegTable& st, int wide);
 hipError_t grad_mfma(const CallCtx& c, const bf16* Big, int wide, const bf16* Small, const OutTable& out,
-                     int accumulate, bool wide_first);
+                     int accumulate, bool wide_first, float* partial);
 
 // One projection of a group that shares its input, for the two shared-input kernels:
 // rows: Z_p = s_pk x_k A_pk (M = A_pk, output rows_out [T, ldz]); grad: dA_pk = x_k^T G_p

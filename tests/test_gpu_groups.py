@@ -103,8 +103,9 @@ def test_group_small_shapes(dtype, case):
 
 
 def test_group_matches_single_calls():
-    """Each projection's Y, dA_k, dB_k are bit-identical to the single-projection entry points;
-    dX agrees with the sum of the single calls' dX up to their bf16 roundings."""
+    """Each projection's Y and dB_k are bit-identical to the single-projection entry points, dA_k
+    up to the order of fp32 additions; dX agrees with the sum of the single calls' dX up to
+    their bf16 roundings."""
     from tests.parity_util import run_hip
     ins = _group_inputs(1024, 256, [384, 128], [300, 724], [[16, 32], [8, 64]], torch.bfloat16, seed=29)
     out = run_group(ins)
@@ -113,7 +114,10 @@ def test_group_matches_single_calls():
         one = run_hip(i)
         assert torch.equal(one["Y"], out["Y"][p])
         for k in range(2):
-            assert torch.equal(one["dA"][k], out["dA"][p][k]) and torch.equal(one["dB"][k], out["dB"][p][k])
+            assert torch.equal(one["dB"][k], out["dB"][p][k])
+            # dA: the same products in fp32; the single call may add them in another order
+            # (it splits a task's tokens over blocks when few blocks would run)
+            assert relerr(np64(one["dA"][k]), np64(out["dA"][p][k])) <= 1e-5
         total = np64(one["dX"]) if total is None else total + np64(one["dX"])
     assert relerr(np64(out["dX"]), total) <= 1e-2
 

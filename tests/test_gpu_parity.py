@@ -151,6 +151,28 @@ def test_empty_batch_on_gpu():
     assert not dA[0].any() and not dB[0].any()
 
 
+@pytest.mark.parametrize("case", [
+    (4096, 256, 384, [4096], [32], 0),                 # one task: 16 token ranges per gradient block column
+    (2100, 256, 128, [1500, 0, 590], [16, 8, 64], 7),  # ranges that come out empty for the short tasks
+    (3000, 128, 640, [700, 2300], [128, 8], 0),        # rank 128, ragged range ends
+])
+def test_token_split_gradients(case):
+    """Few tasks and few columns: the gradient kernels split each task's tokens over blocks and a
+    second kernel adds the ranges in order.  Oracle parity, accumulate mode, determinism."""
+    T, h, d, tokens, ranks, lead = case
+    inp = _inputs(T, h, d, tokens, ranks, torch.bfloat16, lead=lead, seed=37)
+    base = run_hip(inp)
+    check_full(inp, base, TOL[torch.bfloat16], label=f"token split {case}")
+    again = run_hip(inp)
+    pre_a = [torch.full_like(t, 0.5) for t in base["dA"]]
+    pre_b = [torch.full_like(t, -1.5) for t in base["dB"]]
+    acc = run_hip(inp, accumulate=True, preset_grads=(pre_a, pre_b))
+    for k in range(len(ranks)):
+        assert torch.equal(base["dA"][k], again["dA"][k]) and torch.equal(base["dB"][k], again["dB"][k])
+        assert relerr(np64(acc["dA"][k]), np64(base["dA"][k]) + 0.5) <= 1e-6
+        assert relerr(np64(acc["dB"][k]), np64(base["dB"][k]) - 1.5) <= 1e-6
+
+
 def _same_bits(a, b, K):
     assert torch.equal(a["Y"], b["Y"]) and torch.equal(a["dX"], b["dX"])
     for k in range(K):
