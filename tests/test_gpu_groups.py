@@ -92,6 +92,7 @@ def check_group(ins, out, tol, label=""):
     (1000, 192, [320, 64, 128], [100, 0, 333, 500], [[8, 24, 128, 64], [16, 16, 16, 16], [64, 8, 8, 32]], 7),  # MFMA in bf16
     (1537, 448, [576, 192, 192, 64], [1, 255, 257, 1024], [[64, 32, 8, 16]] * 4, 0),                   # four projections
     (640, 256, [256], [320, 320], [[16, 32]], 0),                                                      # a group of one
+    (17000, 128, [128, 64], [9000, 0, 7990], [[16, 8, 64], [32, 32, 8]], 3),                           # 64-row tiles in the shared pass
     (900, 128, [192, 64], [130, 700], [[128, 8], [64, 128]], 3),                                       # two projections, rank 128
     (777, 320, [64, 64, 128, 64], [300, 77, 400], [[8, 32, 16], [32, 8, 8], [16, 16, 16], [24, 8, 32]], 0),  # four, ranks <= 32
 ])

@@ -173,6 +173,39 @@ def test_token_split_gradients(case):
         assert relerr(np64(acc["dB"][k]), np64(base["dB"][k]) - 1.5) <= 1e-6
 
 
+def _random_case(seed, mfma):
+    """A seeded random problem: K in 0..12 tasks with empty ones, ragged lengths, uncovered rows."""
+    g = torch.Generator().manual_seed(1000 + seed)
+    ri = lambda lo, hi: int(torch.randint(lo, hi + 1, (1,), generator=g))
+    K = ri(0, 12)
+    tokens = [0 if ri(0, 5) == 0 else ri(1, 700) for _ in range(K)]
+    lead, tail = ri(0, 40), ri(0, 40)
+    T = max(lead + sum(tokens) + tail, 1)
+    if mfma:
+        h, d = 64 * ri(1, 8), 64 * ri(1, 8)
+        ranks = [8 * ri(1, 16) for _ in range(K)]
+    else:
+        h, d = ri(1, 300), ri(1, 300)
+        ranks = [ri(1, 128) for _ in range(K)]
+    scal = [0.25 * ri(1, 12) for _ in range(K)]
+    return T, h, d, tokens, ranks, lead, scal
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_mfma_path(seed):
+    T, h, d, tokens, ranks, lead, scal = _random_case(seed, True)
+    inp = _inputs(T, h, d, tokens, ranks, torch.bfloat16, lead=lead, seed=seed, scal=scal)
+    check_full(inp, run_hip(inp), TOL[torch.bfloat16], label=f"random mfma seed {seed}: {(T, h, d, tokens, ranks, lead)}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("seed", range(4))
+def test_random_shapes_generic_path(seed, dtype):
+    T, h, d, tokens, ranks, lead, scal = _random_case(100 + seed, False)
+    inp = _inputs(T, h, d, tokens, ranks, dtype, lead=lead, seed=seed, scal=scal)
+    check_full(inp, run_hip(inp), TOL[dtype], label=f"random generic seed {seed}: {(T, h, d, tokens, ranks, lead)}")
+
+
 def test_hip_graph_capture_and_replay():
     """The entry points allocate nothing and keep all metadata in kernel arguments, so a forward +
     backward pair can be captured into a HIP graph; every replay (with eager work between the
