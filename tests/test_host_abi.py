@@ -25,6 +25,25 @@ def test_exports_match_header(mb):
         assert hasattr(mb.lib, name), name
 
 
+def test_header_is_plain_c_and_links(mb, tmp_path):
+    """include/mlora.h compiles as C (gcc, -std=c99 -pedantic) and a C program linked against the
+    library can call the argument-checking entry points."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    exe = str(tmp_path / "abi_check")
+    libdir = os.path.dirname(mb.LIB_PATH)
+    cmd = [gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c", "abi_check.c"), "-o", exe, "-L", libdir, "-l:libmlora.so",
+           "-Wl,-rpath," + libdir]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "abi_check: ok" in r.stdout, r.stdout + r.stderr
+
+
 def test_status_strings(mb):
     for code in range(8):
         assert mb.lib.mlora_status_string(code)
