@@ -19,6 +19,8 @@
 // leaves the CU as full 128-byte row segments.
 #pragma once
 
+#include <type_traits>
+
 #include "mfma_staging.h"
 #include "mlora_common.h"
 
@@ -157,11 +159,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   };
 
   // the idx-th of the PER_TILE wave-wide loads of contraction tile kt
-  auto issue_one = [&](int kt, int idx, char* sa, char* sb) {
+  auto issue_one = [&](const char* atile, const char* btile, int idx, char* sa, char* sb) {
     if (idx < LPW)
-      load_lds_16B_sbase(abase + (size_t)kt * (BK * 2), aoff[idx], sa + (wave + NW * idx) * 1024);
+      load_lds_16B_sbase(atile, aoff[idx], sa + (wave + NW * idx) * 1024);
     else
-      load_lds_16B_sbase(bbase + (size_t)kt * bstep, boff[idx - LPW], sb + (wave + NW * (idx - LPW)) * 1024);
+      load_lds_16B_sbase(btile, boff[idx - LPW], sb + (wave + NW * (idx - LPW)) * 1024);
+  };
+  auto issue_tile = [&](int kt, char* sa, char* sb) {
+    const char* atile = abase + (size_t)kt * (BK * 2);
+    const char* btile = bbase + (size_t)kt * bstep;
+#pragma unroll
+    for (int idx = 0; idx < PER_TILE; ++idx) issue_one(atile, btile, idx, sa, sb);
   };
 
   const int l32 = lane & 31, lhi = lane >> 5;
@@ -203,9 +211,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   bf16x8 af[2][FM], bfr[2][FN];
 
   // one MFMA step on fragment set `cur`; behind MFMA number m: fragment reads 2m, 2m+1 of the
-  // next step into set `cur ^ 1` (if rd), and, in the last PER_TILE slots, one load of tile ld_kt (if ld)
-  auto step = [&](int cur, bool rd, const char* rsa, const char* rsb, int rks, bool ld, int ld_kt, char* lsa,
+  // next step into set `cur ^ 1` (if rd), and, in the last PER_TILE slots, one load of tile ld_kt
+  // (if ld).  `rd` and `ld` are std::true_type / std::false_type in the steady-state loop, so that
+  // it compiles to straight-line code (a conditional branch per slot costs the wave more than the
+  // slot's memory instruction), and plain bools in the few tiles around it.
+  auto step = [&](int cur, auto rd, const char* rsa, const char* rsb, int rks, auto ld, int ld_kt, char* lsa,
                   char* lsb) {
+    const char* atile = abase + (size_t)ld_kt * (BK * 2);
+    const char* btile = bbase + (size_t)ld_kt * bstep;
 #pragma unroll
     for (int m = 0; m < NMF; ++m) {
       const int i = m / FN, j = m % FN;
@@ -214,10 +227,28 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
         read_op(rsa, rsb, rks, 2 * m, af[cur ^ 1], bfr[cur ^ 1]);
         if (2 * m + 1 < NOPS) read_op(rsa, rsb, rks, 2 * m + 1, af[cur ^ 1], bfr[cur ^ 1]);
       }
-      if (ld && m >= NMF - PER_TILE) issue_one(ld_kt, m - (NMF - PER_TILE), lsa, lsb);
+      if (ld && m >= NMF - PER_TILE) issue_one(atile, btile, m - (NMF - PER_TILE), lsa, lsb);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+
+  // contraction tile kt in stage s: steps 0..2, barrier, step 3 with the reads of (kt+1, step 0)
+  // (if rd) and the loads of tile kt+2 into stage s (if ld)
+  auto tile = [&](int kt, auto stage, auto rd, auto ld) {
+    constexpr int s = decltype(stage)::value;
+    step(0, yes, sA[s], sB[s], 1, no, 0, nullptr, nullptr);
+    step(1, yes, sA[s], sB[s], 2, no, 0, nullptr, nullptr);
+    step(0, yes, sA[s], sB[s], 3, no, 0, nullptr, nullptr);
+    // tile kt+1 has landed (this wave's part), every fragment of tile kt is in registers
+    wait_vmcnt<0>();
+    wait_lds();
+    __builtin_amdgcn_s_barrier();
+    step(1, rd, sA[s ^ 1], sB[s ^ 1], 0, ld, kt + 2, sA[s], sB[s]);
+  };
+  constexpr std::integral_constant<int, 0> stage0{};
+  constexpr std::integral_constant<int, 1> stage1{};
 
   // ---- main contraction loop (unrolled by the two stages so that stage addresses are constants)
   static_assert(NS == 2 && KS == 4, "loop below is written for a double buffer of 4-step tiles");
@@ -227,11 +258,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   for (int sg = 0; sg < NSEG; ++sg) {
     set_operands(ga.A[sg], ga.Bm[sg], ga.Kd[sg]);
     const int KT = ga.Kd[sg] / BK;
-#pragma unroll
-    for (int idx = 0; idx < PER_TILE; ++idx) issue_one(0, idx, sA[0], sB[0]);
+    issue_tile(0, sA[0], sB[0]);
     if (KT > 1) {
-#pragma unroll
-      for (int idx = 0; idx < PER_TILE; ++idx) issue_one(1, idx, sA[1], sB[1]);
+      issue_tile(1, sA[1], sB[1]);
       wait_vmcnt<PER_TILE>();
     } else {
       wait_vmcnt<0>();
@@ -240,22 +269,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
 #pragma unroll
     for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
     __builtin_amdgcn_sched_barrier(0);
-    for (int kt0 = 0; kt0 < KT; kt0 += 2) {
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const int kt = kt0 + s;
-        if (kt < KT) {
-          step(0, true, sA[s], sB[s], 1, false, 0, nullptr, nullptr);
-          step(1, true, sA[s], sB[s], 2, false, 0, nullptr, nullptr);
-          step(0, true, sA[s], sB[s], 3, false, 0, nullptr, nullptr);
-          // tile kt+1 has landed (this wave's part), every fragment of tile kt is in registers
-          wait_vmcnt<0>();
-          wait_lds();
-          __builtin_amdgcn_s_barrier();
-          step(1, kt + 1 < KT, sA[s ^ 1], sB[s ^ 1], 0, kt + 2 < KT, kt + 2, sA[s], sB[s]);
-        }
-      }
+    // steady state, two tiles per trip: both have a successor to read and a tile to load
+    int kt = 0;
+    for (; kt + 3 < KT; kt += 2) {
+      tile(kt, stage0, yes, yes);
+      tile(kt + 1, stage1, yes, yes);
     }
+    // the last two or three tiles
+    if (kt < KT) tile(kt, stage0, kt + 1 < KT, kt + 2 < KT);
+    if (kt + 1 < KT) tile(kt + 1, stage1, kt + 2 < KT, false);
+    if (kt + 2 < KT) tile(kt + 2, stage0, false, false);
   }  // operand pairs
 
   // ---- LoRA extension steps (the stages are free now: every load has landed and every wave
