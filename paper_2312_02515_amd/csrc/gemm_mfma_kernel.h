@@ -69,6 +69,10 @@ struct GemmArgs {
 // Contraction tiles of 32 in a 4- or 5-stage ring (deeper prefetch, half-line requests) were
 // measured 7 % slower on the K-contiguous operands and equal on the forward's W tile.
 // ------------------------------------------------------------------------------------------
+// 16 zero bytes in device memory: where the lanes of a LoRA tile point whose row, column or rank
+// index lies outside the task (a direct-to-LDS load cannot be masked)
+__device__ uint4 g_zero_chunk;
+
 template <int WAVES_M, int WAVES_N, bool NN, int BK, int NSEG>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmArgs<NSEG> ga) {
   static_assert(BK == 64, "contraction tile");
@@ -210,15 +214,89 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
 
   bf16x8 af[2][FM], bfr[2][FN];
 
+  // ---- LoRA contraction tiles.  After the last operand pair's base tiles the same pipeline
+  // runs one more tile per (task k that owns rows of this block, 64 ranks of it): its A side is
+  // the task's slice of L (Z or G, zero outside the task's rows), its B side the same ranks of
+  // R_k (B_k or A_k), fetched into the same LDS layouts by the same direct loads -- so the LoRA
+  // term costs ceil(r_k / 64) more tiles on the same accumulators and no exposed load latency.
+  const int rend = (row0 + BM) < M ? (row0 + BM) : M;
+  struct LoraTile {
+    int sg, k, q0, lo, hi;
+  };
+  int n_lora = 0;
+  for (int sg = 0; sg < NSEG; ++sg)
+    for (int k = 0; k < ga.K; ++k) {
+      const int lo = ga.off[k] > row0 ? ga.off[k] : row0;
+      const int hi = ga.off[k + 1] < rend ? ga.off[k + 1] : rend;
+      if (lo < hi) n_lora += (ga.rank[sg][k] + BK - 1) / BK;
+    }
+  auto find_lora = [&](int e) {
+    LoraTile t{0, 0, 0, 0, 0};
+    for (int sg = 0; sg < NSEG; ++sg)
+      for (int k = 0; k < ga.K; ++k) {
+        const int lo = ga.off[k] > row0 ? ga.off[k] : row0;
+        const int hi = ga.off[k + 1] < rend ? ga.off[k + 1] : rend;
+        if (lo >= hi) continue;
+        const int nch = (ga.rank[sg][k] + BK - 1) / BK;
+        if (e >= 0 && e < nch) t = LoraTile{sg, k, e * BK, lo, hi};
+        e -= nch;
+      }
+    return t;
+  };
+  // what the load slots of a step fetch: base tile kt of the current operand pair, or a LoRA tile
+  struct LoadCtx {
+    bool lora;
+    const char* atile;
+    const char* btile;
+    LoraTile lt;
+  };
+  auto base_ctx = [&](int kt) {
+    return LoadCtx{false, abase + (size_t)kt * (BK * 2), bbase + (size_t)kt * bstep, LoraTile{0, 0, 0, 0, 0}};
+  };
+  const char* const zeros = reinterpret_cast<const char*>(&g_zero_chunk);
+  auto issue_lora_one = [&](const LoraTile& t, int idx, char* sa, char* sb) {
+    if (idx < LPW) {
+      const bf16* L = ga.L[t.sg];
+      const int ldz = ga.ldz[t.sg];
+      const int w = wave + NW * idx;
+      const int rl = RPI * w + lane / CPR;
+      const int c = (lane % CPR) ^ ((rl / RW) % CPR);
+      const int row = row0 + rl, q = t.q0 + c * 8;
+      const char* p = (row >= t.lo && row < t.hi && q < ldz) ? reinterpret_cast<const char*>(L + (size_t)row * ldz + q) : zeros;
+      load_lds_16B(p, sa + w * 1024);
+    } else {
+      const int r = ga.rank[t.sg][t.k];
+      const bf16* Rk = static_cast<const bf16*>(ga.R[t.sg].p[t.k]);
+      const int w = wave + NW * (idx - LPW);
+      const char* p = zeros;
+      if (NN) {
+        const int kr = 2 * w + (lane >> 5);
+        const int c = (lane & 31) ^ ((kr & 3) << 2);
+        const int q = t.q0 + kr, n = col0 + c * 8;
+        if (q < r && n < N) p = reinterpret_cast<const char*>(Rk + (size_t)q * N + n);
+      } else {
+        const int rl = RPI * w + lane / CPR;
+        const int c = (lane % CPR) ^ ((rl / RW) % CPR);
+        const int n = col0 + rl, q = t.q0 + c * 8;
+        if (n < N && q < r) p = reinterpret_cast<const char*>(Rk + (size_t)n * r + q);
+      }
+      load_lds_16B(p, sb + w * 1024);
+    }
+  };
+  auto issue_ctx_one = [&](const LoadCtx& lc, int idx, char* sa, char* sb) {
+    if (lc.lora)
+      issue_lora_one(lc.lt, idx, sa, sb);
+    else
+      issue_one(lc.atile, lc.btile, idx, sa, sb);
+  };
+
   // one MFMA step on fragment set `cur`; behind MFMA number m: fragment reads 2m, 2m+1 of the
-  // next step into set `cur ^ 1` (if rd), and, in the last PER_TILE slots, one load of tile ld_kt
-  // (if ld).  `rd` and `ld` are std::true_type / std::false_type in the steady-state loop, so that
-  // it compiles to straight-line code (a conditional branch per slot costs the wave more than the
-  // slot's memory instruction), and plain bools in the few tiles around it.
-  auto step = [&](int cur, auto rd, const char* rsa, const char* rsb, int rks, auto ld, int ld_kt, char* lsa,
+  // next step into set `cur ^ 1` (if rd), and, in the last PER_TILE slots, one load of the tile
+  // `lc` describes (if ld).  `rd` and `ld` are std::true_type / std::false_type in the steady-state
+  // loop, so that it compiles to straight-line code (a conditional branch per slot costs the wave
+  // more than the slot's memory instruction), and plain bools in the few tiles around it.
+  auto step = [&](int cur, auto rd, const char* rsa, const char* rsb, int rks, auto ld, const LoadCtx& lc, char* lsa,
                   char* lsb) {
-    const char* atile = abase + (size_t)ld_kt * (BK * 2);
-    const char* btile = bbase + (size_t)ld_kt * bstep;
 #pragma unroll
     for (int m = 0; m < NMF; ++m) {
       const int i = m / FN, j = m % FN;
@@ -227,25 +305,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
         read_op(rsa, rsb, rks, 2 * m, af[cur ^ 1], bfr[cur ^ 1]);
         if (2 * m + 1 < NOPS) read_op(rsa, rsb, rks, 2 * m + 1, af[cur ^ 1], bfr[cur ^ 1]);
       }
-      if (ld && m >= NMF - PER_TILE) issue_one(atile, btile, m - (NMF - PER_TILE), lsa, lsb);
+      if (ld && m >= NMF - PER_TILE) issue_ctx_one(lc, m - (NMF - PER_TILE), lsa, lsb);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
+  const LoadCtx none{false, nullptr, nullptr, LoraTile{0, 0, 0, 0, 0}};
 
-  // contraction tile kt in stage s: steps 0..2, barrier, step 3 with the reads of (kt+1, step 0)
-  // (if rd) and the loads of tile kt+2 into stage s (if ld)
-  auto tile = [&](int kt, auto stage, auto rd, auto ld) {
+  // the tile in stage s: steps 0..2, barrier, step 3 with the reads of the next tile's step 0
+  // (if rd) and the loads of the tile after that, `lc`, into stage s (if ld)
+  auto tile = [&](auto stage, auto rd, auto ld, const LoadCtx& lc) {
     constexpr int s = decltype(stage)::value;
-    step(0, yes, sA[s], sB[s], 1, no, 0, nullptr, nullptr);
-    step(1, yes, sA[s], sB[s], 2, no, 0, nullptr, nullptr);
-    step(0, yes, sA[s], sB[s], 3, no, 0, nullptr, nullptr);
-    // tile kt+1 has landed (this wave's part), every fragment of tile kt is in registers
+    step(0, yes, sA[s], sB[s], 1, no, none, nullptr, nullptr);
+    step(1, yes, sA[s], sB[s], 2, no, none, nullptr, nullptr);
+    step(0, yes, sA[s], sB[s], 3, no, none, nullptr, nullptr);
+    // the next tile has landed (this wave's part), every fragment of this tile is in registers
     wait_vmcnt<0>();
     wait_lds();
     __builtin_amdgcn_s_barrier();
-    step(1, rd, sA[s ^ 1], sB[s ^ 1], 0, ld, kt + 2, sA[s], sB[s]);
+    step(1, rd, sA[s ^ 1], sB[s ^ 1], 0, ld, lc, sA[s], sB[s]);
   };
   constexpr std::integral_constant<int, 0> stage0{};
   constexpr std::integral_constant<int, 1> stage1{};
@@ -258,9 +337,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   for (int sg = 0; sg < NSEG; ++sg) {
     set_operands(ga.A[sg], ga.Bm[sg], ga.Kd[sg]);
     const int KT = ga.Kd[sg] / BK;
-    issue_tile(0, sA[0], sB[0]);
-    if (KT > 1) {
-      issue_tile(1, sA[1], sB[1]);
+    const int VT = KT + (sg == NSEG - 1 ? n_lora : 0);  // tiles of this pass: base tiles, then LoRA tiles
+    auto ctx_of = [&](int v) {
+      if (v < KT) return base_ctx(v);
+      return LoadCtx{true, nullptr, nullptr, find_lora(v - KT)};
+    };
+    auto issue_whole = [&](const LoadCtx& lc, char* sa, char* sb) {
+#pragma unroll
+      for (int idx = 0; idx < PER_TILE; ++idx) issue_ctx_one(lc, idx, sa, sb);
+    };
+    issue_whole(base_ctx(0), sA[0], sB[0]);
+    if (VT > 1) {
+      issue_whole(ctx_of(1), sA[1], sB[1]);
       wait_vmcnt<PER_TILE>();
     } else {
       wait_vmcnt<0>();
@@ -269,73 +357,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
 #pragma unroll
     for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
     __builtin_amdgcn_sched_barrier(0);
-    // steady state, two tiles per trip: both have a successor to read and a tile to load
-    int kt = 0;
-    for (; kt + 3 < KT; kt += 2) {
-      tile(kt, stage0, yes, yes);
-      tile(kt + 1, stage1, yes, yes);
+    // steady state, two base tiles per trip: both have a successor to read and a base tile to load
+    int v = 0;
+    for (; v + 3 < KT; v += 2) {
+      tile(stage0, yes, yes, base_ctx(v + 2));
+      tile(stage1, yes, yes, base_ctx(v + 3));
     }
-    // the last two or three tiles
-    if (kt < KT) tile(kt, stage0, kt + 1 < KT, kt + 2 < KT);
-    if (kt + 1 < KT) tile(kt + 1, stage1, kt + 2 < KT, false);
-    if (kt + 2 < KT) tile(kt + 2, stage0, false, false);
+    // the last base tiles and the LoRA tiles
+    for (; v < VT; v += 2) {
+      tile(stage0, v + 1 < VT, v + 2 < VT, v + 2 < VT ? ctx_of(v + 2) : none);
+      if (v + 1 < VT) tile(stage1, v + 2 < VT, v + 3 < VT, v + 3 < VT ? ctx_of(v + 3) : none);
+    }
   }  // operand pairs
-
-  // ---- LoRA extension steps (the stages are free now: every load has landed and every wave
-  // passed the last barrier after its last fragment read)
-  auto ext_compute = [&](int ksteps) {
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks < ksteps) {
-#pragma unroll
-        for (int op = 0; op < NOPS; ++op) read_op(sA0, sB0, ks, op, af[0], bfr[0]);
-#pragma unroll
-        for (int m = 0; m < NMF; ++m) {
-          const int i = m / FN, j = m % FN;
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[0][j], af[0][i], acc[i][j], 0, 0, 0);
-        }
-      }
-    }
-  };
-  const int rend = (row0 + BM) < M ? (row0 + BM) : M;
-  for (int sg = 0; sg < NSEG; ++sg) {
-    const bf16* __restrict__ L = ga.L[sg];
-    const int ldz = ga.ldz[sg];
-    for (int k = 0; k < ga.K; ++k) {
-      const int lo = ga.off[k] > row0 ? ga.off[k] : row0;
-      const int hi = ga.off[k + 1] < rend ? ga.off[k + 1] : rend;
-      if (lo >= hi) continue;
-      const int r = ga.rank[sg][k];
-      const bf16* Rk = static_cast<const bf16*>(ga.R[sg].p[k]);
-      for (int q0 = 0; q0 < r; q0 += BK) {
-        __syncthreads();
-        for (int e = tid; e < BM * CPR; e += NT) {
-          const int rl = e / CPR, c = e % CPR;
-          const int row = row0 + rl, q = q0 + c * 8;
-          uint4 v = make_uint4(0, 0, 0, 0);
-          if (row >= lo && row < hi && q < ldz) v = *(const uint4*)(L + (size_t)row * ldz + q);
-          *(uint4*)(sA0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
-        }
-        for (int e = tid; e < BM * CPR; e += NT) {
-          uint4 v = make_uint4(0, 0, 0, 0);
-          if (NN) {
-            const int kr = e >> 5, c = e & 31;
-            const int q = q0 + kr, n = col0 + c * 8;
-            if (q < r && n < N) v = *(const uint4*)(Rk + (size_t)q * N + n);
-            *(uint4*)(sB0 + kr * 512 + ((c ^ ((kr & 3) << 2)) << 4)) = v;
-          } else {
-            const int rl = e / CPR, c = e % CPR;
-            const int n = col0 + rl, q = q0 + c * 8;
-            if (n < N && q < r) v = *(const uint4*)(Rk + (size_t)n * r + q);
-            *(uint4*)(sB0 + rl * ROWB + ((c ^ ((rl / RW) % CPR)) << 4)) = v;
-          }
-        }
-        __syncthreads();
-        const int left = (r - q0 + 15) / 16;
-        ext_compute(left < KS ? left : KS);
-      }
-    }
-  }
 
   // ---- output: through LDS, so that the tile leaves as 16 B per lane in full row segments of
   // the wave's sub-tile.  Each wave owns WM x WN x 2 bytes of the stage arrays (row stride WN x 2
