@@ -23,12 +23,15 @@
  * d output features, Y = X W), A_k is [h, r_k], B_k is [r_k, d].  Every matrix is
  * dense row-major with no padding between rows.
  *
- * Memory: the library owns nothing and allocates nothing.  Every pointer marked
+ * Memory: the entry points declared in this header own nothing and allocate
+ * nothing, on the host or on the device.  Every pointer marked
  * DEVICE is GPU memory allocated by the caller on the current HIP device; every
  * pointer marked HOST is ordinary host memory that is read before the call
  * returns (the caller may free or reuse it on return).  All work is enqueued on
  * `hip_stream` (a hipStream_t passed as void*; NULL = the default stream) and
- * the calls return without waiting for it.
+ * the calls return without waiting for it.  (The test and measurement switches
+ * of mlora_testing.h are not part of this contract: the timing aid there creates
+ * HIP events.)
  *
  * Errors: every call validates its arguments first and returns a status; on any
  * status other than MLORA_OK no kernel has been launched and no output has been
@@ -90,7 +93,9 @@ typedef struct {
 size_t mlora_lora_saved_bytes(const mlora_problem* p);
 
 /* Size in bytes of the scratch `workspace` either call needs (the larger of the two).
- * The workspace carries nothing from one call to the next.  Returns 0 if invalid. */
+ * Depends on the sizes in `p` only (T, h, d, dtype, split positions, ranks), never on the
+ * addresses it holds.  The workspace carries nothing from one call to the next.
+ * Returns 0 if invalid. */
 size_t mlora_lora_workspace_bytes(const mlora_problem* p);
 
 /* Argument check only (no GPU needed): the status mlora_lora_fwd would return for `p`
@@ -169,33 +174,18 @@ const char* mlora_status_string(mlora_status s);
 /* hipError_t (as int) of the last HIP failure seen by this thread's calls; 0 if none. */
 int mlora_last_hip_error(void);
 
-/* Selects which kernels the two entry points use, for testing and measurement (bit mask):
- *   0 (default) fastest applicable path: MFMA kernels when the problem is bf16, h and d are
- *               multiples of 64, every rank is a multiple of 8 and all buffers are 16-byte
- *               aligned; the generic kernels otherwise,
- *   bit 0       generic kernels for the two base products,
- *   bit 1       generic kernels for the low-rank products (3 = generic everywhere).
- * Returns the previous value.  Process-wide. */
-int mlora_set_kernel_path(int path);
-
-/* Measurement aid.  While enabled, every launch of the MFMA kernels by this process is bracketed
- * by a pair of HIP events recorded on the launch stream (at most 16384 launches are kept; the
- * events are created on first use and live until the process ends).  Returns the previous
- * setting. */
-int mlora_profile_kernels(int enable);
-
-/* Kinds of kernels the measurement aid tells apart, and the unit their work is counted in. */
-#define MLORA_PROFILE_GEMM  0  /* base products with their LoRA steps; algorithmic flops
-                                  (2 M N K plus 2 t_k r_k N per task)                          */
-#define MLORA_PROFILE_ROWS  1  /* s x A and s dy B^T; algorithmic bytes (activation rows read
-                                  once, result written once, adapter matrices read once)       */
-#define MLORA_PROFILE_GRAD  2  /* dA_k and dB_k; algorithmic bytes                             */
-#define MLORA_PROFILE_KINDS 3
-
-/* Waits for the recorded launches to finish; for each kind returns the sum of their durations
- * in milliseconds, the sum of their work in that kind's unit, and their count, through the
- * non-NULL pointers (HOST arrays of MLORA_PROFILE_KINDS entries), and forgets them. */
-mlora_status mlora_profile_kernels_read(double* ms_total, double* units_total, int* launches);
+/* Which kernels the calls will run for `p` (bit mask), so that a caller can tell the fast path
+ * from the fallback before it launches anything:
+ *   0      bf16 MFMA kernels everywhere,
+ *   bit 0  the two base products run the generic (plain vector ALU, roughly 100 times slower)
+ *          kernels,
+ *   bit 1  the low-rank products run the generic kernels (3 = generic everywhere).
+ * The MFMA kernels take bf16 problems whose h and d are multiples of 64, whose ranks are
+ * multiples of 8 and whose W, A_k, B_k are 16-byte aligned; the answer assumes that the buffers
+ * passed to the calls (X, Y, dY, dX, saved, workspace) are 16-byte aligned too, as device
+ * allocations are -- a call handed a misaligned buffer falls back for that call.  Returns -1 if
+ * the problem is invalid.  Honours mlora_set_kernel_path (mlora_testing.h). */
+int mlora_lora_kernel_path(const mlora_problem* p);
 
 #ifdef __cplusplus
 }

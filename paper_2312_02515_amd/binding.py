@@ -1,4 +1,4 @@
-"""Thin ctypes binding over the C ABI of libmlora.so (see include/mlora.h).
+"""Thin ctypes binding over the C ABI of libmlora.so (see include/mlora.h, include/mlora_testing.h).
 
 Argument marshalling only: every arithmetic step runs in the library's HIP
 kernels.  PyTorch is used for device memory and streams.  There is no CPU
@@ -27,8 +27,10 @@ STATUS_NAMES = {0: "MLORA_OK", 1: "MLORA_ERR_NULL", 2: "MLORA_ERR_SHAPE", 3: "ML
 EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_validate", "mlora_lora_fwd",
            "mlora_lora_bwd", "mlora_lora_recompute_workspace_bytes", "mlora_lora_fwd_nosave",
            "mlora_lora_bwd_recompute", "mlora_lora_group_validate", "mlora_lora_group_workspace_bytes",
-           "mlora_lora_group_fwd", "mlora_lora_group_bwd", "mlora_status_string", "mlora_last_hip_error", "mlora_set_kernel_path", "mlora_profile_kernels",
-           "mlora_profile_kernels_read"]
+           "mlora_lora_group_fwd", "mlora_lora_group_bwd", "mlora_status_string", "mlora_last_hip_error",
+           "mlora_lora_kernel_path"]
+# include/mlora_testing.h: test and measurement switches
+TESTING_EXPORTS = ["mlora_set_kernel_path", "mlora_profile_kernels", "mlora_profile_kernels_read"]
 
 
 class MloraError(RuntimeError):
@@ -95,6 +97,8 @@ def _load() -> ctypes.CDLL:
     l.mlora_status_string.argtypes = [ctypes.c_int]
     l.mlora_last_hip_error.restype = ctypes.c_int
     l.mlora_last_hip_error.argtypes = []
+    l.mlora_lora_kernel_path.restype = ctypes.c_int
+    l.mlora_lora_kernel_path.argtypes = [pp]
     l.mlora_set_kernel_path.restype = ctypes.c_int
     l.mlora_set_kernel_path.argtypes = [ctypes.c_int]
     l.mlora_profile_kernels.restype = ctypes.c_int
@@ -154,6 +158,10 @@ class Problem:
 
     def validate(self) -> int:
         return int(lib.mlora_lora_validate(ctypes.byref(self.c)))
+
+    def kernel_path(self) -> int:
+        """0 = MFMA kernels; bit 0 / bit 1 = generic kernels for the base / low-rank products."""
+        return int(lib.mlora_lora_kernel_path(ctypes.byref(self.c)))
 
     def alloc_saved(self) -> torch.Tensor:
         return torch.empty(self.saved_bytes(), dtype=torch.uint8, device=self.W.device)

@@ -46,10 +46,19 @@ void fill_common(gemmk::GemmArgs<NSEG>* a, bf16* C, int M, int N, const SegTable
   a->C = C;
   a->M = M;
   a->N = N;
-  a->tiles_m = (M + BM - 1) / BM;
   a->tiles_n = (N + BN - 1) / BN;
   a->K = st.K;
   for (int k = 0; k <= kMaxK; ++k) a->off[k] = st.off[k];
+  // rows of the virtual axis the grid tiles: every row range of the call (before the first
+  // task, each task, after the last task) rounded up to whole 32-row MFMA fragments
+  long long mv = 0;
+  int prev = 0;
+  for (int r = 0; r < st.K + 2; ++r) {
+    const int b1 = r <= st.K ? st.off[r] : M;
+    mv += (b1 - prev + 31) / 32 * 32;
+    prev = b1;
+  }
+  a->tiles_m = (int)((mv + BM - 1) / BM);
 }
 
 template <int NSEG>

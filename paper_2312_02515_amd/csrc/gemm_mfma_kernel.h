@@ -17,6 +17,14 @@
 // The MFMA takes the weight fragment as its first operand so that each lane ends up with four
 // consecutive output columns of one row; the output tile goes through LDS once more so that it
 // leaves the CU as full 128-byte row segments.
+//
+// Rows: the grid tiles a *virtual* row axis on which every row range of the call (the rows before
+// the first task, each task's rows, the rows after the last task) is padded to a multiple of 32,
+// the row count of one MFMA fragment.  A fragment therefore never holds rows of two tasks, and a
+// task's LoRA tile runs its MFMAs only on that task's fragments: no row ever meets another
+// task's adapter (not even multiplied by zero, which would turn an Inf or NaN of a diverged
+// adapter into NaN in its neighbours' rows).  Padding rows re-read the range's last row and
+// are not stored.  When every range is a multiple of 32 rows the virtual axis is the real one.
 #pragma once
 
 #include <type_traits>
@@ -39,7 +47,7 @@ constexpr int BM = 256, BN = 256;
 template <int NSEG>
 struct GemmArgs {
   bf16* C;
-  int M, N, tiles_m, tiles_n;
+  int M, N, tiles_m, tiles_n;            // tiles_m counts tiles of the virtual row axis
   int K;                                 // tasks
   int off[kMaxK + 1];                    // split positions (rows of C)
   const bf16* A[NSEG];                   // [M, Kd_g]
@@ -111,11 +119,49 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
   const int in_g = t - group * gsize;
   const int tm = first_m + in_g % gm, tn = in_g / gm;
-  const int row0 = tm * BM, col0 = tn * BN;
+  const int col0 = tn * BN;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  // ---- the block's 8 fragments of 32 virtual rows: first real row, number of real rows
+  // (0 = beyond the last row: such a fragment re-reads row M-1 and stores nothing) and task
+  // (-1 = rows of no task).  Range s of the call is [b_s, b_{s+1}) with b_0 = 0, b_{1+k} = off[k],
+  // b_{K+2} = M; task k owns range 1 + k.
+  constexpr int NFR = BM / 32;
+  __shared__ int s_frow[NFR], s_fn[NFR], s_ftask[NFR];
+  if (tid < NFR) {
+    const int v0 = tm * BM + 32 * tid;
+    int vstart = 0, prev = 0, frow = M - 1, fn = 0, ftask = -1;
+    for (int r = 0; r < ga.K + 2; ++r) {
+      const int b1 = r <= ga.K ? ga.off[r] : M;
+      const int len = b1 - prev, vlen = (len + 31) & ~31;
+      if (v0 >= vstart && v0 < vstart + vlen) {
+        const int o = v0 - vstart;
+        frow = prev + o;
+        fn = (len - o) < 32 ? (len - o) : 32;
+        ftask = (r >= 1 && r <= ga.K) ? r - 1 : -1;
+      }
+      vstart += vlen;
+      prev = b1;
+    }
+    s_frow[tid] = frow;
+    s_fn[tid] = fn;
+    s_ftask[tid] = ftask;
+  }
+  __syncthreads();
+  auto frag_row = [&](int f) { return __builtin_amdgcn_readfirstlane(s_frow[f]); };
+  auto frag_n = [&](int f) { return __builtin_amdgcn_readfirstlane(s_fn[f]); };
+  auto frag_task = [&](int f) { return __builtin_amdgcn_readfirstlane(s_ftask[f]); };
+  const int row0 = frag_row(0);  // the block's lowest real row
+  // real row behind row rl (0..255) of the block's tile; rows of one wave-wide load (8 or fewer
+  // consecutive rows) lie in one fragment, so f is wave-uniform there
+  auto real_row = [&](int rl) {
+    const int f = rl >> 5, o = rl & 31;
+    const int n = frag_n(f);
+    return frag_row(f) + (o < n ? o : (n > 0 ? n - 1 : 0));
+  };
 
   // Accumulators in AccVGPRs: naming one "a" register operand makes the compiler select the
   // AGPR form of the MFMAs, which keeps the accumulator traffic off the VGPR ports that the
@@ -141,8 +187,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       {
         const int rl = RPI * w + lane / CPR;
         const int c = (lane % CPR) ^ ((rl / RW) % CPR);
-        int gr = row0 + rl;
-        gr = gr < M ? gr : M - 1;
+        const int gr = real_row(rl);
         aoff[it] = (unsigned)(((size_t)(gr - row0) * Kd + c * 8) * 2);
       }
       if (NN) {
@@ -215,30 +260,28 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   bf16x8 af[2][FM], bfr[2][FN];
 
   // ---- LoRA contraction tiles.  After the last operand pair's base tiles the same pipeline
-  // runs one more tile per (task k that owns rows of this block, 64 ranks of it): its A side is
-  // the task's slice of L (Z or G, zero outside the task's rows), its B side the same ranks of
+  // runs one more tile per (task k that owns fragments of this block, 64 ranks of it): its A side
+  // is the task's slice of L (Z or G; zeros for the other fragments), its B side the same ranks of
   // R_k (B_k or A_k), fetched into the same LDS layouts by the same direct loads -- so the LoRA
   // term costs ceil(r_k / 64) more tiles on the same accumulators and no exposed load latency.
-  const int rend = (row0 + BM) < M ? (row0 + BM) : M;
+  // The fragments of one task are consecutive, so the block's tasks are the runs of s_ftask.
   struct LoraTile {
-    int sg, k, q0, lo, hi;
+    int sg, k, q0;
   };
   int n_lora = 0;
   for (int sg = 0; sg < NSEG; ++sg)
-    for (int k = 0; k < ga.K; ++k) {
-      const int lo = ga.off[k] > row0 ? ga.off[k] : row0;
-      const int hi = ga.off[k + 1] < rend ? ga.off[k + 1] : rend;
-      if (lo < hi) n_lora += (ga.rank[sg][k] + BK - 1) / BK;
+    for (int f = 0; f < NFR; ++f) {
+      const int k = frag_task(f);
+      if (k >= 0 && (f == 0 || frag_task(f - 1) != k)) n_lora += (ga.rank[sg][k] + BK - 1) / BK;
     }
   auto find_lora = [&](int e) {
-    LoraTile t{0, 0, 0, 0, 0};
+    LoraTile t{0, -1, 0};
     for (int sg = 0; sg < NSEG; ++sg)
-      for (int k = 0; k < ga.K; ++k) {
-        const int lo = ga.off[k] > row0 ? ga.off[k] : row0;
-        const int hi = ga.off[k + 1] < rend ? ga.off[k + 1] : rend;
-        if (lo >= hi) continue;
+      for (int f = 0; f < NFR; ++f) {
+        const int k = frag_task(f);
+        if (k < 0 || (f > 0 && frag_task(f - 1) == k)) continue;
         const int nch = (ga.rank[sg][k] + BK - 1) / BK;
-        if (e >= 0 && e < nch) t = LoraTile{sg, k, e * BK, lo, hi};
+        if (e >= 0 && e < nch) t = LoraTile{sg, k, e * BK};
         e -= nch;
       }
     return t;
@@ -251,7 +294,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     LoraTile lt;
   };
   auto base_ctx = [&](int kt) {
-    return LoadCtx{false, abase + (size_t)kt * (BK * 2), bbase + (size_t)kt * bstep, LoraTile{0, 0, 0, 0, 0}};
+    return LoadCtx{false, abase + (size_t)kt * (BK * 2), bbase + (size_t)kt * bstep, LoraTile{0, -1, 0}};
   };
   const char* const zeros = reinterpret_cast<const char*>(&g_zero_chunk);
   auto issue_lora_one = [&](const LoraTile& t, int idx, char* sa, char* sb) {
@@ -261,8 +304,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       const int w = wave + NW * idx;
       const int rl = RPI * w + lane / CPR;
       const int c = (lane % CPR) ^ ((rl / RW) % CPR);
-      const int row = row0 + rl, q = t.q0 + c * 8;
-      const char* p = (row >= t.lo && row < t.hi && q < ldz) ? reinterpret_cast<const char*>(L + (size_t)row * ldz + q) : zeros;
+      const int q = t.q0 + c * 8;
+      const bool mine = frag_task(rl >> 5) == t.k;  // wave-uniform: the 8 rows of this load share a fragment
+      const char* p = (mine && q < ldz) ? reinterpret_cast<const char*>(L + (size_t)real_row(rl) * ldz + q) : zeros;
       load_lds_16B(p, sa + w * 1024);
     } else {
       const int r = ga.rank[t.sg][t.k];
@@ -290,17 +334,32 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       issue_one(lc.atile, lc.btile, idx, sa, sb);
   };
 
+  // Which of the wave's FM fragments take part in a tile: all of them in a base tile, the
+  // fragments of task k in a LoRA tile of task k (the others' MFMAs are skipped).
+  struct FragOn {
+    bool on[FM];
+  };
+  auto frags_of = [&](int k) {  // k < 0: base tile
+    FragOn f;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) f.on[i] = k < 0 || frag_task(wm * FM + i) == k;
+    return f;
+  };
+
   // one MFMA step on fragment set `cur`; behind MFMA number m: fragment reads 2m, 2m+1 of the
   // next step into set `cur ^ 1` (if rd), and, in the last PER_TILE slots, one load of the tile
   // `lc` describes (if ld).  `rd` and `ld` are std::true_type / std::false_type in the steady-state
   // loop, so that it compiles to straight-line code (a conditional branch per slot costs the wave
-  // more than the slot's memory instruction), and plain bools in the few tiles around it.
+  // more than the slot's memory instruction), and plain bools in the few tiles around it; `fo` is
+  // std::true_type there (base tiles: every fragment) and a FragOn in the tiles around it.
   auto step = [&](int cur, auto rd, const char* rsa, const char* rsb, int rks, auto ld, const LoadCtx& lc, char* lsa,
-                  char* lsb) {
+                  char* lsb, const auto& fo) {
 #pragma unroll
     for (int m = 0; m < NMF; ++m) {
       const int i = m / FN, j = m % FN;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+      bool on = true;
+      if constexpr (!std::is_same_v<std::decay_t<decltype(fo)>, std::true_type>) on = fo.on[i];
+      if (on) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
       if (rd && m < RSLOTS) {
         read_op(rsa, rsb, rks, 2 * m, af[cur ^ 1], bfr[cur ^ 1]);
         if (2 * m + 1 < NOPS) read_op(rsa, rsb, rks, 2 * m + 1, af[cur ^ 1], bfr[cur ^ 1]);
@@ -311,20 +370,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
-  const LoadCtx none{false, nullptr, nullptr, LoraTile{0, 0, 0, 0, 0}};
+  const LoadCtx none{false, nullptr, nullptr, LoraTile{0, -1, 0}};
 
   // the tile in stage s: steps 0..2, barrier, step 3 with the reads of the next tile's step 0
-  // (if rd) and the loads of the tile after that, `lc`, into stage s (if ld)
-  auto tile = [&](auto stage, auto rd, auto ld, const LoadCtx& lc) {
+  // (if rd) and the loads of the tile after that, `lc`, into stage s (if ld); `fo` as in step()
+  auto tile = [&](auto stage, auto rd, auto ld, const LoadCtx& lc, const auto& fo) {
     constexpr int s = decltype(stage)::value;
-    step(0, yes, sA[s], sB[s], 1, no, none, nullptr, nullptr);
-    step(1, yes, sA[s], sB[s], 2, no, none, nullptr, nullptr);
-    step(0, yes, sA[s], sB[s], 3, no, none, nullptr, nullptr);
+    step(0, yes, sA[s], sB[s], 1, no, none, nullptr, nullptr, fo);
+    step(1, yes, sA[s], sB[s], 2, no, none, nullptr, nullptr, fo);
+    step(0, yes, sA[s], sB[s], 3, no, none, nullptr, nullptr, fo);
     // the next tile has landed (this wave's part), every fragment of this tile is in registers
     wait_vmcnt<0>();
     wait_lds();
     __builtin_amdgcn_s_barrier();
-    step(1, rd, sA[s ^ 1], sB[s ^ 1], 0, ld, lc, sA[s], sB[s]);
+    step(1, rd, sA[s ^ 1], sB[s ^ 1], 0, ld, lc, sA[s], sB[s], fo);
   };
   constexpr std::integral_constant<int, 0> stage0{};
   constexpr std::integral_constant<int, 1> stage1{};
@@ -360,13 +419,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     // steady state, two base tiles per trip: both have a successor to read and a base tile to load
     int v = 0;
     for (; v + 3 < KT; v += 2) {
-      tile(stage0, yes, yes, base_ctx(v + 2));
-      tile(stage1, yes, yes, base_ctx(v + 3));
+      tile(stage0, yes, yes, base_ctx(v + 2), yes);
+      tile(stage1, yes, yes, base_ctx(v + 3), yes);
     }
     // the last base tiles and the LoRA tiles
+    auto frags_at = [&](int u) { return frags_of(u < KT ? -1 : find_lora(u - KT).k); };
     for (; v < VT; v += 2) {
-      tile(stage0, v + 1 < VT, v + 2 < VT, v + 2 < VT ? ctx_of(v + 2) : none);
-      if (v + 1 < VT) tile(stage1, v + 2 < VT, v + 3 < VT, v + 3 < VT ? ctx_of(v + 3) : none);
+      tile(stage0, v + 1 < VT, v + 2 < VT, v + 2 < VT ? ctx_of(v + 2) : none, frags_at(v));
+      if (v + 1 < VT) tile(stage1, v + 2 < VT, v + 3 < VT, v + 3 < VT ? ctx_of(v + 3) : none, frags_at(v + 1));
     }
   }  // operand pairs
 
@@ -404,10 +464,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     const int r = ORPI * it + lane / OCH, cp = lane % OCH;
     const int c = cp ^ oswz(r);
     const uint4 v = *(const uint4*)(ep + r * OROWB + cp * 16);
-    const int grow = row0 + wm * WM + r, gcol = col0 + wn * WN + c * 8;
+    const int f = (wm * WM + r) >> 5, o = r & 31;  // the row's fragment of the block (WM is a multiple of 32)
+    const int grow = s_frow[f] + o, gcol = col0 + wn * WN + c * 8;
     // non-temporal: the output is not read again by this launch, so it should not displace the
     // operand strips in the L2 / Infinity Cache (measured +0.7 % on the whole forward + backward)
-    if (grow < M && gcol < N)
+    if (o < s_fn[f] && gcol < N)
       __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4*)(C + (size_t)grow * N + gcol));
   }
 }

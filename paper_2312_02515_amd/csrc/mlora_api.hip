@@ -2,6 +2,7 @@
 // No kernel lives here.
 #include <atomic>
 
+#include "../../include/mlora_testing.h"
 #include "mlora_common.h"
 
 namespace mlora {
@@ -74,24 +75,31 @@ void fill_ctx(const mlora_problem* p, void* stream, CallCtx* c) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-// The MFMA GEMMs take bf16 problems whose feature sizes are multiples of 64, whose ranks are
-// multiples of 8 and whose buffers are 16-byte aligned; everything else runs the generic kernels.
-bool mfma_shapes_ok(const mlora_problem* p) {
+// The MFMA kernels take bf16 problems whose feature sizes are multiples of 64, whose ranks are
+// multiples of 8 (mfma_sizes_ok) and whose buffers are 16-byte aligned; everything else runs the
+// generic kernels.
+bool mfma_sizes_ok(const mlora_problem* p) {
   if (p->dtype != MLORA_BF16 || p->T < 1) return false;
   if (!gemm_mfma_ok((int)p->T, (int)p->d, (int)p->h) || !gemm_mfma_ok((int)p->T, (int)p->h, (int)p->d)) return false;
-  if (!aligned16(p->W)) return false;
-  for (int k = 0; k < p->K; ++k) {
-    if (p->ranks[k] % 8 != 0 || !aligned16(p->A[k]) || !aligned16(p->B[k])) return false;
-  }
+  for (int k = 0; k < p->K; ++k)
+    if (p->ranks[k] % 8 != 0) return false;
+  return true;
+}
+
+bool mfma_shapes_ok(const mlora_problem* p) {
+  if (!mfma_sizes_ok(p) || !aligned16(p->W)) return false;
+  for (int k = 0; k < p->K; ++k)
+    if (!aligned16(p->A[k]) || !aligned16(p->B[k])) return false;
   return true;
 }
 
 bool mfma_gemm_applies(const mlora_problem* p) { return !(g_kernel_path.load() & 1) && mfma_shapes_ok(p); }
 bool mfma_lowrank_applies(const mlora_problem* p) { return !(g_kernel_path.load() & 2) && mfma_shapes_ok(p); }
 
-// Scratch for the token-split form of the gradient kernels (0 when they do not split)
+// Scratch for the token-split form of the gradient kernels (0 when they do not split).  A
+// function of the sizes alone: a size query must not change its answer with the addresses.
 size_t grad_scratch_bytes(const mlora_problem* p) {
-  if (!mfma_shapes_ok(p) || p->K == 0) return 0;
+  if (!mfma_sizes_ok(p) || p->K == 0) return 0;
   CallCtx c;
   fill_ctx(p, nullptr, &c);
   const size_t a = grad_partial_bytes(c.st, c.h), b = grad_partial_bytes(c.st, c.d);
@@ -422,6 +430,11 @@ const char* mlora_status_string(mlora_status s) {
 }
 
 int mlora_last_hip_error(void) { return g_last_hip_error; }
+
+int mlora_lora_kernel_path(const mlora_problem* p) {
+  if (validate(p) != MLORA_OK) return -1;
+  return (mfma_gemm_applies(p) ? 0 : 1) | (mfma_lowrank_applies(p) ? 0 : 2);
+}
 
 int mlora_set_kernel_path(int path) { return g_kernel_path.exchange(path); }
 

@@ -182,10 +182,12 @@ def make_workload_inputs(wl: Workload, proj_index: int, device="cpu", seed: int 
                        device=device, seed=seed, sigma_w=wl.sigma_w, proj_id=proj_index)
 
 
-def sample_rows(seg_offsets: Sequence[int], T: int, per_adapter: int, seed: int) -> List[int]:
+def sample_rows(seg_offsets: Sequence[int], T: int, per_adapter: int, seed: int, tile: int = 256) -> List[int]:
     """Rows for sampled checks: for each non-empty segment its first and last row
-    and `per_adapter` seeded draws; plus the rows on both sides of every segment
-    boundary and one row from each uncovered range."""
+    and `per_adapter` seeded draws; the rows on both sides of every segment
+    boundary; one row from each uncovered range; and, so that no output tile of
+    `tile` rows goes unchecked, the first row, the last row and one seeded draw
+    of every such tile (tile = 0 leaves these out)."""
     g = torch.Generator(device="cpu")
     g.manual_seed(int(seed))
     rows = set()
@@ -205,4 +207,10 @@ def sample_rows(seg_offsets: Sequence[int], T: int, per_adapter: int, seed: int)
         rows.add(0)
     if int(seg_offsets[-1]) < T:
         rows.add(T - 1)
+    if tile > 0 and T > 0:
+        n_tiles = (T + tile - 1) // tile
+        draws = torch.randint(0, tile, (n_tiles,), generator=g)
+        for i in range(n_tiles):
+            lo, hi = i * tile, min(T, (i + 1) * tile)
+            rows.update((lo, hi - 1, min(lo + int(draws[i]), hi - 1)))
     return sorted(rows)

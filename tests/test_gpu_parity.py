@@ -6,7 +6,8 @@ import pytest
 import torch
 
 from paper_2312_02515_amd import workloads as wl
-from tests.parity_util import TOL, check_full, check_sampled, np64, relerr, run_hip
+from tests.parity_util import (LORA_TERM_CASES, MFMA_SMALL_CASES, TOL, check_full, check_sampled, np64, relerr,
+                               run_hip, zero_base_weight)
 
 pytestmark = pytest.mark.gpu
 
@@ -38,16 +39,29 @@ def test_tiny_f32_workload():
     (257, 64, 64, [], [], 0),                                         # no adapters: plain linear
     (640, 256, 320, [64, 192, 128, 256], [8, 16, 32, 64], 0),         # tile-aligned mixed ranks
     (700, 328, 264, [1, 63, 65, 300, 200], [64, 3, 128, 17, 40], 30),  # odd everything, rank up to 128
-    # shapes the MFMA kernels take (h, d multiples of 64, ranks multiples of 8), ragged in every other way
-    (1000, 192, 320, [100, 0, 333, 500], [8, 24, 128, 64], 7),        # rank 128, empty segment, tails
-    (900, 128, 64, [130, 700], [16, 8], 3),                           # narrow output, small ranks
-    (1537, 448, 576, [1, 255, 257, 1024], [64, 32, 8, 16], 0),        # one-token task, tile-straddling tasks
-])
+] + MFMA_SMALL_CASES)  # and the shapes the MFMA kernels take, ragged in every other way
 def test_small_shapes(dtype, case):
     T, h, d, tokens, ranks, lead = case
     inp = _inputs(T, h, d, tokens, ranks, dtype, lead=lead, seed=11, scal=[0.5 + 0.25 * i for i in range(len(ranks))])
     out = run_hip(inp)
     check_full(inp, out, TOL[dtype], label=f"{case}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("case", LORA_TERM_CASES)
+def test_lora_term_alone(dtype, case):
+    """W = 0: every task's rows of Y and dX are the LoRA terms of Eq. "forward" and
+    Eq. "grad_output" alone, so the tolerance applies to those terms directly, task by task
+    (bf16: the terms folded into the MFMA base-product kernel as extra contraction tiles);
+    rows of no task must come out as exact zeros."""
+    T, h, d, tokens, ranks, lead = case
+    inp = zero_base_weight(_inputs(T, h, d, tokens, ranks, dtype, lead=lead, seed=19,
+                                   scal=[0.5 + 0.25 * i for i in range(len(ranks))]))
+    out = run_hip(inp)
+    check_full(inp, out, TOL[dtype], label=f"W=0 {case}")
+    off = inp.seg_offsets
+    assert not out["Y"][:off[0]].any() and not out["Y"][off[-1]:].any()
+    assert not out["dX"][:off[0]].any() and not out["dX"][off[-1]:].any()
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -99,21 +113,96 @@ def test_deterministic():
         assert torch.equal(a["dA"][k], b["dA"][k]) and torch.equal(a["dB"][k], b["dB"][k])
 
 
-def test_isolation_on_gpu():
-    """Changing task 1's data and adapter leaves task 0's and 2's results bit-identical."""
-    inp = _inputs(768, 256, 256, [256, 256, 256], [8, 16, 8], torch.bfloat16, seed=21)
+ISOLATION_CASES = [
+    # T, h, d, tokens, ranks, lead, the task that is disturbed
+    (768, 256, 256, [256, 256, 256], [8, 16, 8], 0, 1),        # tile-aligned tasks
+    (600, 256, 320, [100, 157, 300], [8, 16, 8], 11, 1),       # tasks share 256-row tiles and 32-row fragments
+    (1100, 192, 128, [5, 1, 700, 333], [64, 128, 16, 8], 3, 1),  # a one-token task between its neighbours
+    (1500, 128, 256, [700, 90, 650], [16, 64, 32], 0, 0),      # the first task; long enough for token-split gradients
+]
+
+
+def _others_identical(a, b, inp, j):
+    off = inp.seg_offsets
+    K = len(inp.ranks)
+    lo, hi = off[j], off[j + 1]
+    for name in ("Y", "dX"):
+        assert torch.equal(a[name][:lo], b[name][:lo]) and torch.equal(a[name][hi:], b[name][hi:]), name
+    for k in range(K):
+        if k != j:
+            assert torch.equal(a["dA"][k], b["dA"][k]) and torch.equal(a["dB"][k], b["dB"][k]), k
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("case", ISOLATION_CASES)
+def test_isolation_on_gpu(dtype, case):
+    """Each adapter uses only its own portion of the data (section 3.3.1): changing task j's
+    rows, adapter and scaling leaves every other task's results (and the rows of no task)
+    bit-identical, also where tasks share tiles of the kernels."""
+    T, h, d, tokens, ranks, lead, j = case
+    inp = _inputs(T, h, d, tokens, ranks, dtype, lead=lead, seed=21)
     a = run_hip(inp)
-    inp.X[256:512] += 1.0
-    inp.dY[256:512] *= -2.0
-    inp.A[1].mul_(3.0)
-    inp.B[1].add_(0.25)
-    inp.scalings[1] = 7.0
+    lo, hi = inp.seg_offsets[j], inp.seg_offsets[j + 1]
+    inp.X[lo:hi] += 1.0
+    inp.dY[lo:hi] *= -2.0
+    inp.A[j].mul_(3.0)
+    inp.B[j].add_(0.25)
+    inp.scalings[j] = 7.0
     b = run_hip(inp)
-    for lo, hi in ((0, 256), (512, 768)):
-        assert torch.equal(a["Y"][lo:hi], b["Y"][lo:hi]) and torch.equal(a["dX"][lo:hi], b["dX"][lo:hi])
-    for k in (0, 2):
-        assert torch.equal(a["dA"][k], b["dA"][k]) and torch.equal(a["dB"][k], b["dB"][k])
-    assert not torch.equal(a["Y"][256:512], b["Y"][256:512])
+    _others_identical(a, b, inp, j)
+    assert not torch.equal(a["Y"][lo:hi], b["Y"][lo:hi])
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("what", ["A", "B", "X", "dY"])
+@pytest.mark.parametrize("case", ISOLATION_CASES)
+def test_isolation_from_non_finite_values(dtype, what, case):
+    """A diverged task (NaN or Inf in its adapter or in its rows) must not leak into its
+    neighbours: their Y, dX, dA_k, dB_k stay finite and bit-identical to a clean run."""
+    T, h, d, tokens, ranks, lead, j = case
+    inp = _inputs(T, h, d, tokens, ranks, dtype, lead=lead, seed=22)
+    a = run_hip(inp)
+    lo, hi = inp.seg_offsets[j], inp.seg_offsets[j + 1]
+    bad = {"A": inp.A[j], "B": inp.B[j], "X": inp.X[lo:hi], "dY": inp.dY[lo:hi]}[what]
+    flat = bad.view(-1)  # whole tensors and row ranges are contiguous: this writes through
+    flat[0::3] = float("nan")
+    flat[1::3] = float("inf")
+    flat[2::3] = -float("inf")
+    b = run_hip(inp)
+    _others_identical(a, b, inp, j)
+    for name in ("Y", "dX"):
+        assert torch.isfinite(b[name][:lo]).all() and torch.isfinite(b[name][hi:]).all()
+
+
+@pytest.mark.parametrize("K", [1, 4, 64])
+def test_batched_equals_separate_calls(K):
+    """One batched call over K tasks against K single-task calls of the library on the same
+    rows (Listing 2 against Listing 1; the launch-count argument of section 3.3.2 changes the
+    number of launches, never the arithmetic): dA_k, dB_k bit-identical, every task's rows of
+    Y and dX within the tolerance of each other and of the oracle."""
+    from paper_2312_02515_amd import binding as mb
+    g = torch.Generator().manual_seed(77 + K)
+    tokens = [int(torch.randint(1, 1 + 4096 // K, (1,), generator=g)) for _ in range(K)]
+    ranks = [8 * (1 + k % 4) for k in range(K)]
+    lead = 5
+    T = lead + sum(tokens) + 3
+    h, d = 256, 320
+    inp = _inputs(T, h, d, tokens, ranks, torch.bfloat16, lead=lead, seed=51, scal=[0.5 + 0.03 * k for k in range(K)])
+    batched = run_hip(inp)
+    check_full(inp, batched, TOL[torch.bfloat16], label=f"batched K={K}")
+    off = inp.seg_offsets
+    for k in range(K):
+        lo, hi = off[k], off[k + 1]
+        one = wl.Inputs(X=inp.X[lo:hi].contiguous(), W=inp.W, dY=inp.dY[lo:hi].contiguous(), A=[inp.A[k]], B=[inp.B[k]],
+                        seg_offsets=[0, hi - lo], ranks=[ranks[k]], scalings=[inp.scalings[k]])
+        sep = run_hip(one)
+        # The separate call runs other launch shapes (few rows: the contraction of s x A is split
+        # over waves, a task's tokens over blocks), so fp32 sums may differ in their last bits and
+        # a bf16 intermediate in its last place here and there: far inside the tolerance.
+        assert relerr(np64(sep["dA"][0]), np64(batched["dA"][k])) <= 1e-3, k
+        assert relerr(np64(sep["dB"][0]), np64(batched["dB"][k])) <= 1e-3, k
+        assert relerr(np64(sep["Y"]), np64(batched["Y"][lo:hi])) <= 2e-3, k
+        assert relerr(np64(sep["dX"]), np64(batched["dX"][lo:hi])) <= 2e-3, k
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])

@@ -16,13 +16,18 @@ def mb():
     return binding
 
 
-def test_exports_match_header(mb):
-    text = open(os.path.join(ROOT, "include", "mlora.h")).read()
+@pytest.mark.parametrize("header,exports", [("mlora.h", "EXPORTS"), ("mlora_testing.h", "TESTING_EXPORTS")])
+def test_exports_match_header(mb, header, exports):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(mlora_[a-z_]+)\s*\(", text))
-    assert declared == set(mb.EXPORTS)
+    assert declared == set(getattr(mb, exports))
     for name in declared:
         assert hasattr(mb.lib, name), name
+
+
+def test_every_header_is_covered(mb):
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["mlora.h", "mlora_testing.h"]
 
 
 def test_header_is_plain_c_and_links(mb, tmp_path):
@@ -194,6 +199,39 @@ def test_empty_input_is_a_noop(mb):
 def test_kernel_path_switch(mb):
     old = mb.set_kernel_path(1)
     assert mb.set_kernel_path(old) == 1
+
+
+def test_kernel_path_query(mb):
+    """A caller can learn, before launching, whether the MFMA kernels or the ~100x slower generic
+    kernels will run: bf16, h and d multiples of 64, ranks multiples of 8, 16-byte aligned W, A_k, B_k."""
+    fast = _problem(mb, T=64, h=128, d=192, ranks=(8, 16))
+    assert fast.kernel_path() == 0
+    assert _problem(mb, T=64, h=32, d=48).kernel_path() == 3           # h, d not multiples of 64
+    assert _problem(mb, T=64, h=128, d=192, ranks=(8, 4)).kernel_path() == 3  # a rank not a multiple of 8
+    odd = _problem(mb, T=64, h=128, d=192, ranks=(8, 16))
+    odd.c.W = 0x5008
+    assert odd.kernel_path() == 3                                        # misaligned W
+    f32 = _problem(mb, T=64, h=128, d=192, ranks=(8, 16))
+    f32.c.dtype = mb.MLORA_F32
+    assert f32.kernel_path() == 3
+    assert _problem(mb, off=(0, 40, 30)).kernel_path() == -1             # invalid problem
+    old = mb.set_kernel_path(1)
+    try:
+        assert fast.kernel_path() == 1
+    finally:
+        mb.set_kernel_path(old)
+
+
+def test_workspace_size_does_not_depend_on_addresses(mb):
+    """One task of many tokens: the gradient kernels split its tokens over blocks and need
+    partial-sum scratch; the size query gives the same answer whatever the pointers are."""
+    a = _problem(mb, T=4096, h=256, d=384, off=(0, 4096), ranks=(32,), s=(1.0,))
+    b = _problem(mb, T=4096, h=256, d=384, off=(0, 4096), ranks=(32,), s=(1.0,))
+    b.c.W = 0x5002
+    b._A[0] = 0x2006
+    assert a.kernel_path() == 0 and b.kernel_path() == 3
+    assert a.workspace_bytes() == b.workspace_bytes() > 4096 * 32 * 2
+    assert a.recompute_workspace_bytes() == b.recompute_workspace_bytes()
 
 
 def test_workloads_match_benchmark_description():
