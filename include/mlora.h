@@ -127,6 +127,23 @@ mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* d
                             void* dX, float* const* dA, float* const* dB, int accumulate,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* mlora_lora_bwd for callers that cannot allocate device memory or carry a workspace pointer
+ * (code under HIP graph capture set up elsewhere, tight serving-style loops, harnesses that
+ * forbid hipMalloc): the scratch the backward needs lives in a fixed array of
+ * MLORA_STATIC_SCRATCH_BYTES inside the library's device image instead of a caller's
+ * workspace.  The call allocates nothing on the host or the device; arguments, results and
+ * errors are those of mlora_lora_bwd without `workspace`, and the results are bit-identical
+ * to it.  A problem whose mlora_lora_workspace_bytes(p) exceeds MLORA_STATIC_SCRATCH_BYTES is
+ * refused with MLORA_ERR_WORKSPACE before anything is launched.  Every GPU the library runs on
+ * holds its own copy of the array until the process ends; its address is looked up on the first
+ * call on each device.  All calls on one GPU share that array: two calls that may overlap in
+ * time (different streams, different threads) race -- use mlora_lora_bwd with separate
+ * workspaces there. */
+#define MLORA_STATIC_SCRATCH_BYTES (32u << 20)
+mlora_status mlora_lora_bwd_static(const mlora_problem* p, const void* X, const void* dY, const void* saved,
+                                   void* dX, float* const* dA, float* const* dB, int accumulate,
+                                   void* hip_stream);
+
 /* Activation-recompute variant of the pair above, for training runs that checkpoint activations
  * (the single-GPU setup of section 4.1 does): nothing is kept between the two calls; the
  * backward call recomputes s_k x_k A_k from X (one more pass over X, 2 t_k h r_k flops per task)

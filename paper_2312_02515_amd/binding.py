@@ -28,7 +28,8 @@ EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_v
            "mlora_lora_bwd", "mlora_lora_recompute_workspace_bytes", "mlora_lora_fwd_nosave",
            "mlora_lora_bwd_recompute", "mlora_lora_group_validate", "mlora_lora_group_workspace_bytes",
            "mlora_lora_group_fwd", "mlora_lora_group_bwd", "mlora_status_string", "mlora_last_hip_error",
-           "mlora_lora_kernel_path"]
+           "mlora_lora_kernel_path", "mlora_lora_bwd_static"]
+MLORA_STATIC_SCRATCH_BYTES = 32 << 20
 # include/mlora_testing.h: test and measurement switches
 TESTING_EXPORTS = ["mlora_set_kernel_path", "mlora_profile_kernels", "mlora_profile_kernels_read"]
 
@@ -71,6 +72,10 @@ def _load() -> ctypes.CDLL:
     l.mlora_lora_bwd.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                  ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    l.mlora_lora_bwd_static.restype = ctypes.c_int
+    l.mlora_lora_bwd_static.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                        ctypes.c_void_p]
     l.mlora_lora_recompute_workspace_bytes.restype = ctypes.c_size_t
     l.mlora_lora_recompute_workspace_bytes.argtypes = [pp]
     l.mlora_lora_fwd_nosave.restype = ctypes.c_int
@@ -205,6 +210,22 @@ def mlora_lora_bwd(prob: Problem, X: torch.Tensor, dY: torch.Tensor, saved: torc
                             _stream_handle(stream))
     if st != 0:
         raise MloraError(st, "mlora_lora_bwd")
+
+
+def mlora_lora_bwd_static(prob: Problem, X: torch.Tensor, dY: torch.Tensor, saved: torch.Tensor,
+                          dX: Optional[torch.Tensor], dA: List[torch.Tensor], dB: List[torch.Tensor], accumulate: bool,
+                          stream: Optional[torch.cuda.Stream] = None) -> None:
+    """mlora_lora_bwd with the library's own fixed scratch array instead of a workspace."""
+    K = prob.K
+    pa = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dA])
+    pb = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dB])
+    st = lib.mlora_lora_bwd_static(ctypes.byref(prob.c), X.data_ptr(), dY.data_ptr(), saved.data_ptr(),
+                                   dX.data_ptr() if dX is not None else None,
+                                   ctypes.cast(pa, ctypes.POINTER(ctypes.c_void_p)),
+                                   ctypes.cast(pb, ctypes.POINTER(ctypes.c_void_p)), 1 if accumulate else 0,
+                                   _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_bwd_static")
 
 
 def mlora_lora_fwd_nosave(prob: Problem, X: torch.Tensor, Y: torch.Tensor, workspace: torch.Tensor,

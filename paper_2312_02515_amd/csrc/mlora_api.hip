@@ -1,12 +1,41 @@
 // C-ABI entry points of libmlora: argument validation, buffer layout, dispatch.
 // No kernel lives here.
 #include <atomic>
+#include <mutex>
 
 #include "../../include/mlora_testing.h"
 #include "mlora_common.h"
 
+// Scratch of mlora_lora_bwd_static: G and the gradient kernels' partial sums live here instead
+// of in a caller's workspace.  One copy per GPU the library runs on, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[MLORA_STATIC_SCRATCH_BYTES];
+
 namespace mlora {
 namespace {
+
+// `scratch` names a host-side stand-in, not device memory: the array's device address is looked
+// up once per device (each GPU has its own copy at its own address) and only that pointer is
+// ever handed to kernels.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 thread_local int g_last_hip_error = 0;
 std::atomic<int> g_kernel_path{0};
@@ -275,6 +304,23 @@ mlora_status mlora_lora_bwd(const mlora_problem* p, const void* X, const void* d
   fill_ctx(p, hip_stream, &c);
   float* partial = grad_scratch_bytes(p) ? reinterpret_cast<float*>(static_cast<char*>(workspace) + lowrank_bytes(p)) : nullptr;
   return hip_status(backward_impl(p, c, X, dY, saved, workspace, dX, dA, dB, accumulate, partial));
+}
+
+mlora_status mlora_lora_bwd_static(const mlora_problem* p, const void* X, const void* dY, const void* saved, void* dX,
+                                   float* const* dA, float* const* dB, int accumulate, void* hip_stream) {
+  mlora_status st = validate(p);
+  if (st != MLORA_OK) return st;
+  if (p->T > 0 && (X == nullptr || dY == nullptr || saved == nullptr)) return MLORA_ERR_NULL;
+  st = check_grad_tables(p, dA, dB);
+  if (st != MLORA_OK) return st;
+  if (mlora_lora_workspace_bytes(p) > (size_t)MLORA_STATIC_SCRATCH_BYTES) return MLORA_ERR_WORKSPACE;
+  if (p->T == 0 && accumulate) return MLORA_OK;
+  void* ws = nullptr;
+  const hipError_t e = static_scratch(&ws);
+  if (e != hipSuccess) return hip_status(e);
+  // Nothing in the scratch has to start at zero: G is written for every row that is read, the
+  // partial sums are overwritten before the reduction reads them.
+  return mlora_lora_bwd(p, X, dY, saved, dX, dA, dB, accumulate, ws, (size_t)MLORA_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, const void* dY, void* dX,
