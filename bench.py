@@ -125,6 +125,8 @@ def main():
     ap.add_argument("--recompute", action="store_true",
                     help="time the activation-recompute pair of entry points (nothing saved between forward and "
                          "backward; the backward recomputes s x A) instead of the default pair")
+    ap.add_argument("--kernel-path", type=int, default=0,
+                    help="test switch of include/mlora_testing.h (bit mask; 0 = the fastest kernels)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic that calibrates the FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs)")
@@ -143,6 +145,8 @@ def main():
     torch.cuda.set_device(0)
     w = wl.WORKLOADS[WORKLOAD]
     stream = torch.cuda.current_stream()
+    if args.kernel_path:
+        mb.set_kernel_path(args.kernel_path)
 
     projs = []
     for pi, p in enumerate(w.projections):
