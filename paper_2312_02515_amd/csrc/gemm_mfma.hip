@@ -8,9 +8,6 @@
 // base product is launched once over all tasks' rows; the output tile is written once with the
 // LoRA term already in it (no full-size intermediate for the LoRA part of dX exists).
 #include "gemm_mfma_kernel.h"
-#include "gemm_mfma16_kernel.h"
-#include "gemm_mfma_ring_kernel.h"
-#include "gemm_mfma_vs_kernel.h"
 #include "mlora_common.h"
 
 namespace mlora {
@@ -38,17 +35,7 @@ template <bool NN, int NSEG>
 hipError_t launch(const gemmk::GemmArgs<NSEG>& a, hipStream_t stream) {
   const dim3 grid(a.tiles_m * a.tiles_n);
   const int slot = profile_begin(kProfileGemm, algorithmic_flops(a), stream);
-  const int kp = kernel_path_flags();
-  if (kp & 4)
-    hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, NN, 64, NSEG>), grid, dim3(512), 0, stream, a);
-  else if (kp & 8)
-    hipLaunchKernelGGL((gemmvs::k_gemm_mfma_vs<2, 2, NN, NSEG>), grid, dim3(256), 0, stream, a);
-  else if (kp & 16)
-    hipLaunchKernelGGL((gemmr::k_gemm_mfma_ring<2, 4, NN, NSEG>), grid, dim3(512), 0, stream, a);
-  else if (kp & 32)
-    hipLaunchKernelGGL((gemmr::k_gemm_mfma_ring<2, 2, NN, NSEG>), grid, dim3(256), 0, stream, a);
-  else
-    hipLaunchKernelGGL((gemm16::k_gemm_mfma16<2, 4, NN, NSEG>), grid, dim3(512), 0, stream, a);
+  hipLaunchKernelGGL((gemmk::k_gemm_mfma<2, 4, NN, NSEG>), grid, dim3(512), 0, stream, a);
   const hipError_t err = hipGetLastError();
   profile_end(slot, stream);
   return err;

@@ -1,30 +1,48 @@
-// bf16 MFMA GEMM kernel with the LoRA term folded in as extra contraction steps (gfx950).
+// bf16 MFMA GEMM kernel with the LoRA term folded in as extra contraction steps (gfx950),
+// on v_mfma_f32_16x16x32_bf16.
 //
 //   C[M,N] = A[M,Kd] * op(Bm) + rows_k( L[rows_k, :r_k] * R_k )
 //     NN = true  (forward,  Eq. "forward"):      Bm = W [Kd,N] (contraction index = rows of W),  R_k = B_k [r_k, N]
 //     NN = false (backward, Eq. "grad_output"):  Bm = W [N,Kd] (contraction index = columns),     R_k = A_k [N, r_k]
 //
-// Tile 256 x 256 x BK, 8 waves (2 x 4, wave tile 128 x 64), fp32 accumulation in
-// v_mfma_f32_32x32x16_bf16 with the accumulators in AccVGPRs, LDS tiles (BK = 64) filled by
-// direct global->LDS loads (global_load_lds_dwordx4, 16 B per lane) into a double buffer.  A wave-wide direct load
-// fills 1 KiB of contiguous LDS, so the bank-conflict swizzle is applied by choosing which global
-// 16-byte chunk each lane fetches:
-//   * K-contiguous tiles (A, and Bm when !NN): 256 rows x 128 B; chunk c of row r sits at chunk
-//     position c ^ ((r >> 1) & 7); read with ds_read_b128.
-//   * Bm when NN: BK contraction rows x 512 B; chunk c of row k sits at c ^ ((k & 3) << 2); read
-//     with ds_read_b64_tr_b16, which hands each lane four consecutive contraction indices of one
-//     output column -- no transposed copy of W is ever made.
-// The MFMA takes the weight fragment as its first operand so that each lane ends up with four
-// consecutive output columns of one row; the output tile goes through LDS once more so that it
-// leaves the CU as full 128-byte row segments.
+// Why this MFMA shape: under this operator's data the board runs at its power cap, so what a
+// kernel sustains is set by energy per flop.  A 16x16x32 MFMA sums 32 products into each
+// accumulator element, a 32x32x16 MFMA 16: half the accumulator traffic per flop.  A loop of
+// MFMAs plus the LDS fragment reads of this tile shape sustains about 10 % more with the
+// 16x16x32 shape on the same data.
 //
-// Rows: the grid tiles a *virtual* row axis on which every row range of the call (the rows before
-// the first task, each task's rows, the rows after the last task) is padded to a multiple of 32,
-// the row count of one MFMA fragment.  A fragment therefore never holds rows of two tasks, and a
-// task's LoRA tile runs its MFMAs only on that task's fragments: no row ever meets another
-// task's adapter (not even multiplied by zero, which would turn an Inf or NaN of a diverged
-// adapter into NaN in its neighbours' rows).  Padding rows re-read the range's last row and
-// are not stored.  When every range is a multiple of 32 rows the virtual axis is the real one.
+// Tile 256 x 256 x 64, WAVES_M x WAVES_N waves (2 x 4: wave tile WM x WN = 128 x 64), fp32
+// accumulators in AccVGPRs, LDS tiles filled by direct global->LDS loads (16 B per lane) into a
+// double buffer.  A wave-wide direct load fills 1 KiB of contiguous LDS, so the bank-conflict
+// swizzle is applied by choosing which global 16-byte chunk each lane fetches:
+//   * K-contiguous tiles (A, and Bm when !NN): 256 rows x 128 B; chunk c of row r sits at chunk
+//     position c ^ ((r >> 1) & 7); a fragment (16 rows x 32 contraction indices) is one
+//     ds_read_b128 per lane: lane l reads chunk 4 q + l / 16 of row l % 16 (q = which half of the tile).
+//   * Bm when NN: 64 contraction rows x 512 B; chunk c of row k sits at
+//     c ^ (((k & 3) << 2) | (((k >> 3) & 1) << 1)); read with two ds_read_b64_tr_b16 per lane,
+//     which hand it eight consecutive contraction indices of one output column -- no transposed
+//     copy of W is ever made.
+// The weight fragment is the MFMA's first operand, so a lane ends up with four consecutive
+// output columns of one row; the output tile goes through LDS once more so that it leaves the CU
+// as full row segments.
+//
+// Schedule.  A contraction tile is four sub-steps: (first 32 contraction indices, upper half of
+// the wave's rows), (same, lower half), (last 32, upper), (last 32, lower); a sub-step runs
+// 4 x WN/16 MFMAs on 4 row fragments and WN/16 weight fragments.  Row fragments are read one
+// sub-step ahead of their use (two register sets); a weight fragment serves both sub-steps of
+// its half tile and is re-read in place right behind its last MFMA, a sub-step before its next
+// use.  At most one memory instruction rides behind each MFMA:
+//   sub-steps 0..2 of tile kt: MFMAs | LDS reads of the next sub-step's fragments
+//   s_waitcnt vmcnt(0), lgkmcnt(0); barrier  (tile kt+1 visible; every wave holds its last
+//                                             fragments of tile kt in registers: kt's stage is free)
+//   sub-step 3: MFMAs | LDS reads of tile kt+1's first fragments | the direct loads of tile kt+2
+//
+// Rows: the grid tiles a virtual row axis on which every row range of the call (the rows before
+// the first task, each task's rows, the rows after the last task) is padded to a multiple of 32.
+// A 32-row fragment pair therefore never holds rows of two tasks, and a task's LoRA tile runs its
+// MFMAs only on that task's rows: no row ever meets another task's adapter (not even multiplied
+// by zero, which would turn an Inf or NaN of a diverged adapter into NaN in its neighbours'
+// rows).  Padding rows re-read the range's last row and are not stored.
 #pragma once
 
 #include <type_traits>
@@ -38,6 +56,7 @@ namespace gemmk {
 using namespace stage;
 
 constexpr int BM = 256, BN = 256;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // Kernel arguments (passed by value, read with scalar loads).  The contraction may run over
 // NSEG operand pairs in turn, all accumulating into the same output tile:
@@ -59,46 +78,36 @@ struct GemmArgs {
   PtrTable R[NSEG];                      // NN: B_k [r, N]; NT: A_k [N, r]
 };
 
-// ------------------------------------------------------------------------------------------
-// Schedule.  Contraction tiles of 64 (rows of 128 B, so every request to the L2 is a full cache
-// line), double-buffered in LDS; tile kt+1 is fetched while tile kt is computed.  Every memory
-// instruction sits between two MFMAs: issuing a vector-memory load keeps the SIMD's issue port
-// busy for some cycles; when a wave issues its loads back to back the matrix pipe idles
-// meanwhile, when each load follows an MFMA it hides behind that MFMA's 32 cycles.  The same
-// holds for the LDS fragment reads, which run one MFMA step ahead of their use (two register
-// sets of fragments).
-//   tile kt:  steps 0..2: MFMAs on (kt, step s); behind them LDS reads of (kt, step s+1)
-//             s_waitcnt vmcnt(0), lgkmcnt(0); barrier   (tile kt+1 visible; every wave holds its
-//                     last fragments of tile kt in registers, so tile kt's stage is free)
-//             step 3: MFMAs on (kt, step 3); behind them LDS reads of (kt+1, step 0) and the 8
-//                     direct-to-LDS loads of tile kt+2 into tile kt's stage
-// The barrier sits in the middle of the MFMA stream with the next step's fragments already in
-// registers, so no LDS read latency is exposed behind it.
-// Contraction tiles of 32 in a 4- or 5-stage ring (deeper prefetch, half-line requests) were
-// measured 7 % slower on the K-contiguous operands and equal on the forward's W tile.
-// ------------------------------------------------------------------------------------------
 // 16 zero bytes in device memory: where the lanes of a LoRA tile point whose row, column or rank
 // index lies outside the task (a direct-to-LDS load cannot be masked)
 __device__ uint4 g_zero_chunk;
 
-template <int WAVES_M, int WAVES_N, bool NN, int BK, int NSEG>
+
+// c += a x b on a 16 x 16 x 32 bf16 MFMA, accumulating in place in AccVGPRs.  Written as inline
+// assembly with the accumulator as a tied operand: with the builtin the register allocator is
+// free to give the result another register than the input, and in a loop of 128 MFMAs on 32
+// accumulators it then rotates the accumulators through the register file with one copy per
+// MFMA.  Every accumulator is used again at the earliest 16 MFMAs later and read by other
+// instructions only after the main loop's final barrier, so no wait states are owed here.
+__device__ __forceinline__ void mfma_16x16x32(f32x4& c, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+template <int WAVES_M, int WAVES_N, bool NN, int NSEG>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmArgs<NSEG> ga) {
-  static_assert(BK == 64, "contraction tile");
+  constexpr int BK = 64;
   bf16* __restrict__ C = ga.C;
   const int M = ga.M, N = ga.N, tiles_m = ga.tiles_m, tiles_n = ga.tiles_n;
-  constexpr int NS = 2;                        // LDS stages: 2 x (32 + 32) KiB
-  constexpr int KS = BK / 16;                  // MFMA steps per contraction tile
-  constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
+  constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-  constexpr int FM = WM / 32, FN = WN / 32;
-  constexpr int NMF = FM * FN;                 // MFMAs per step
-  constexpr int NOPS = FM + FN;                // fragment reads per step
-  constexpr int RSLOTS = (NOPS + 1) / 2;       // two fragment reads behind each of the first MFMAs
+  constexpr int FM = WM / 16, FN = WN / 16;    // 16-row fragments, 16-column weight fragments of the wave tile
+  constexpr int HM = FM / 2;                   // row fragments per sub-step
+  constexpr int NMF = HM * FN;                 // MFMAs per sub-step
   constexpr int ROWB = BK * 2, CPR = BK / 8, RW = 256 / ROWB, RPI = 1024 / ROWB;
   constexpr int TILE_BYTES = BM * ROWB;        // the NN weight tile (BK x 512 B) has the same size
   constexpr int LPW = TILE_BYTES / 1024 / NW;  // wave-wide loads per wave per operand tile
   constexpr int PER_TILE = 2 * LPW;
-  static_assert(PER_TILE <= NMF && RSLOTS <= NMF, "not enough MFMAs per step to hide the memory instructions");
+  static_assert(WM == 128, "the sub-steps halve a 128-row wave tile");
 
   __shared__ __attribute__((aligned(1024))) char sA0[TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) char sA1[TILE_BYTES];
@@ -107,12 +116,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   char* const sA[2] = {sA0, sA1};
   char* const sB[2] = {sB0, sB1};
 
+  // block -> tile: consecutive block ids go round-robin over the 8 XCDs, so block b is mapped to
+  // position (b % 8) * (tiles / 8) + b / 8 of a grouped order (8 row tiles x all column tiles per
+  // group): the blocks resident on one XCD form an 8 x 4 patch sharing rows of A and columns of
+  // Bm in that XCD's L2
   const int total = tiles_m * tiles_n;
   const int bid = blockIdx.x;
   const int per = total / 8, rem = total % 8;
   const int xcd = bid % 8, local = bid / 8;
   const int t = xcd * per + (xcd < rem ? xcd : rem) + local;
-  constexpr int GM = 8;  // 8 row tiles x 4 column tiles per XCD (4 x 8: 0.4 % faster, 9 % more L2 misses; 16 x 2: 9 % slower)
+  constexpr int GM = 8;
   const int gsize = GM * tiles_n;
   const int group = t / gsize;
   const int first_m = group * GM;
@@ -125,10 +138,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-  // ---- the block's 8 fragments of 32 virtual rows: first real row, number of real rows
-  // (0 = beyond the last row: such a fragment re-reads row M-1 and stores nothing) and task
-  // (-1 = rows of no task).  Range s of the call is [b_s, b_{s+1}) with b_0 = 0, b_{1+k} = off[k],
-  // b_{K+2} = M; task k owns range 1 + k.
+  // ---- the block's 8 pieces of 32 virtual rows: first real row, number of real rows (0 = beyond
+  // the last row: such a piece re-reads row M-1 and stores nothing) and task (-1 = rows of no
+  // task).  Range s of the call is [b_s, b_{s+1}) with b_0 = 0, b_{1+k} = off[k], b_{K+2} = M;
+  // task k owns range 1 + k.
   constexpr int NFR = BM / 32;
   __shared__ int s_frow[NFR], s_fn[NFR], s_ftask[NFR];
   if (tid < NFR) {
@@ -155,21 +168,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   auto frag_n = [&](int f) { return __builtin_amdgcn_readfirstlane(s_fn[f]); };
   auto frag_task = [&](int f) { return __builtin_amdgcn_readfirstlane(s_ftask[f]); };
   const int row0 = frag_row(0);  // the block's lowest real row
-  // real row behind row rl (0..255) of the block's tile; rows of one wave-wide load (8 or fewer
-  // consecutive rows) lie in one fragment, so f is wave-uniform there
+  // real row behind row rl (0..255) of the block's tile; the 8 rows of one wave-wide load lie in
+  // one piece, so f is wave-uniform there
   auto real_row = [&](int rl) {
     const int f = rl >> 5, o = rl & 31;
     const int n = frag_n(f);
     return frag_row(f) + (o < n ? o : (n > 0 ? n - 1 : 0));
   };
-
-  // Accumulators in AccVGPRs: naming one "a" register operand makes the compiler select the
-  // AGPR form of the MFMAs, which keeps the accumulator traffic off the VGPR ports that the
-  // LDS fragment reads write through.
-  {
-    float agpr_hint = 0.f;
-    asm volatile("" : "+a"(agpr_hint));
-  }
 
   // ---- direct-to-LDS loads: wave-uniform base of the tile's rows (advanced per contraction
   // tile with scalar arithmetic) plus a constant 32-bit per-lane byte offset; both are set per
@@ -178,6 +183,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   const char* bbase = nullptr;
   unsigned aoff[LPW], boff[LPW];
   size_t bstep = 0;  // bytes per contraction tile of Bm
+  auto nn_swz = [](int kr) { return ((kr & 3) << 2) | (((kr >> 3) & 1) << 1); };
   auto set_operands = [&](const bf16* A, const bf16* Bm, int Kd) {
     abase = reinterpret_cast<const char*>(A + (size_t)row0 * Kd);
     bbase = NN ? reinterpret_cast<const char*>(Bm + col0) : reinterpret_cast<const char*>(Bm + (size_t)col0 * Kd);
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       }
       if (NN) {
         const int kr = 2 * w + (lane >> 5);
-        const int c = (lane & 31) ^ ((kr & 3) << 2);
+        const int c = (lane & 31) ^ nn_swz(kr);
         int n = col0 + c * 8;
         n = n < N ? n : N - 8;
         boff[it] = (unsigned)(((size_t)kr * N + (n - col0)) * 2);
@@ -207,64 +213,50 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     bstep = (NN ? (size_t)BK * N : (size_t)BK) * 2;
   };
 
-  // the idx-th of the PER_TILE wave-wide loads of contraction tile kt
-  auto issue_one = [&](const char* atile, const char* btile, int idx, char* sa, char* sb) {
-    if (idx < LPW)
-      load_lds_16B_sbase(atile, aoff[idx], sa + (wave + NW * idx) * 1024);
-    else
-      load_lds_16B_sbase(btile, boff[idx - LPW], sb + (wave + NW * (idx - LPW)) * 1024);
-  };
-  auto issue_tile = [&](int kt, char* sa, char* sb) {
-    const char* atile = abase + (size_t)kt * (BK * 2);
-    const char* btile = bbase + (size_t)kt * bstep;
-#pragma unroll
-    for (int idx = 0; idx < PER_TILE; ++idx) issue_one(atile, btile, idx, sa, sb);
-  };
+  // fragment addressing: lane l = 16 kg + r16 holds contraction indices 8 kg .. 8 kg + 7 (of the
+  // 32 of a half tile) of row / column r16 of the fragment
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int fsw = (r16 >> 1) & 7;
+  const int a_row_off = (wm * WM + r16) * ROWB;
+  const int b_row_off = (wn * WN + r16) * ROWB;
+  const int kq = r16 >> 2;
+  const int nn_k = 8 * kg + kq;                   // first of the lane's two 4-row pieces of the W tile
+  const int nn_n = wn * WN + 4 * (r16 & 3);
 
-  const int l32 = lane & 31, lhi = lane >> 5;
-  const int fsw = (l32 / RW) % CPR;
-  const int a_row_off = (wm * WM + l32) * ROWB;
-  const int b_row_off = (wn * WN + l32) * ROWB;
-  const int L16 = lane & 15, blk = lane >> 4, kq = L16 >> 2;
-  const int nn_k = 8 * (blk >> 1) + kq;
-  const int nn_n = wn * WN + 16 * (blk & 1) + 4 * (L16 & 3);
-
-  // fragment read number op (0..NOPS-1) of step ks of the tile in (sa, sb): weight fragments first
-  auto read_op = [&](const char* sa, const char* sb, int ks, int op, bf16x8 (&af)[FM], bf16x8 (&bfr)[FN]) {
-    const int coff = ((2 * ks + lhi) ^ fsw) << 4;
-    if (op < FN) {
-      const int j = op;
-      if (NN) {
-        const int k = 16 * ks + nn_k;
-        const int n = nn_n + 32 * j;
-        const int phys = (n >> 3) ^ (kq << 2);
-        const char* p0 = sb + k * 512 + phys * 16 + (n & 7) * 2;
-        bfr[j] = lds_read_tr_pair(p0, p0 + 4 * 512);
-      } else {
-        bfr[j] = *(const bf16x8*)(sb + b_row_off + j * 32 * ROWB + coff);
-      }
-    } else {
-      const int i = op - FN;
-      af[i] = *(const bf16x8*)(sa + a_row_off + i * 32 * ROWB + coff);
-    }
-  };
-
-  f32x16 acc[FM][FN];
+  f32x4 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  bf16x8 af[2][FM], bfr[2][FN];
+  bf16x8 af[2][HM], bfr[FN];
+
+  // weight fragment j of half q of the tile in sb
+  auto read_b = [&](const char* sb, int q, int j) {
+    if (NN) {
+      const int k = 32 * q + nn_k;
+      const int n = nn_n + 16 * j;
+      const int phys = (n >> 3) ^ ((kq << 2) | ((kg & 1) << 1));
+      const char* p0 = sb + k * 512 + phys * 16 + (n & 7) * 2;
+      bfr[j] = lds_read_tr_pair(p0, p0 + 4 * 512);
+    } else {
+      bfr[j] = *(const bf16x8*)(sb + b_row_off + j * 16 * ROWB + (((4 * q + kg) ^ fsw) << 4));
+    }
+  };
+  // row fragment i (0..HM-1) of half h of the wave's rows, half q of the tile in sa
+  auto read_a = [&](const char* sa, int q, int h, int i, bf16x8 (&af)[HM]) {
+    af[i] = *(const bf16x8*)(sa + a_row_off + (h * HM + i) * 16 * ROWB + (((4 * q + kg) ^ fsw) << 4));
+  };
 
   // ---- LoRA contraction tiles.  After the last operand pair's base tiles the same pipeline
-  // runs one more tile per (task k that owns fragments of this block, 64 ranks of it): its A side
-  // is the task's slice of L (Z or G; zeros for the other fragments), its B side the same ranks of
-  // R_k (B_k or A_k), fetched into the same LDS layouts by the same direct loads -- so the LoRA
-  // term costs ceil(r_k / 64) more tiles on the same accumulators and no exposed load latency.
-  // The fragments of one task are consecutive, so the block's tasks are the runs of s_ftask.
+  // runs one more tile per (task k that owns rows of this block, 64 ranks of it): its A side is
+  // the task's slice of L (Z or G; zeros for the other pieces), its B side the same ranks of R_k
+  // (B_k or A_k), fetched into the same LDS layouts by the same direct loads two tiles ahead --
+  // so the LoRA term costs ceil(r_k / 64) more tiles on the same accumulators and no exposed
+  // load latency.  The pieces of one task are consecutive, so the block's tasks are the runs of
+  // s_ftask.
   struct LoraTile {
     int sg, k, q0;
   };
@@ -286,7 +278,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       }
     return t;
   };
-  // what the load slots of a step fetch: base tile kt of the current operand pair, or a LoRA tile
+  // what the load slots of a tile fetch: base tile kt of the current operand pair, or a LoRA tile
   struct LoadCtx {
     bool lora;
     const char* atile;
@@ -297,7 +289,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     return LoadCtx{false, abase + (size_t)kt * (BK * 2), bbase + (size_t)kt * bstep, LoraTile{0, -1, 0}};
   };
   const char* const zeros = reinterpret_cast<const char*>(&g_zero_chunk);
-  auto issue_lora_one = [&](const LoraTile& t, int idx, char* sa, char* sb) {
+  // wave-wide load number idx (0..LPW-1: A side, LPW..PER_TILE-1: Bm side) of the tile `lc` describes
+  auto issue_one = [&](const LoadCtx& lc, int idx, char* sa, char* sb) {
+    if (!lc.lora) {
+      if (idx < LPW)
+        load_lds_16B_sbase(lc.atile, aoff[idx], sa + (wave + NW * idx) * 1024);
+      else
+        load_lds_16B_sbase(lc.btile, boff[idx - LPW], sb + (wave + NW * (idx - LPW)) * 1024);
+      return;
+    }
+    const LoraTile& t = lc.lt;
     if (idx < LPW) {
       const bf16* L = ga.L[t.sg];
       const int ldz = ga.ldz[t.sg];
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       const int rl = RPI * w + lane / CPR;
       const int c = (lane % CPR) ^ ((rl / RW) % CPR);
       const int q = t.q0 + c * 8;
-      const bool mine = frag_task(rl >> 5) == t.k;  // wave-uniform: the 8 rows of this load share a fragment
+      const bool mine = frag_task(rl >> 5) == t.k;  // wave-uniform: the 8 rows of this load share a piece
       const char* p = (mine && q < ldz) ? reinterpret_cast<const char*>(L + (size_t)real_row(rl) * ldz + q) : zeros;
       load_lds_16B(p, sa + w * 1024);
     } else {
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       const char* p = zeros;
       if (NN) {
         const int kr = 2 * w + (lane >> 5);
-        const int c = (lane & 31) ^ ((kr & 3) << 2);
+        const int c = (lane & 31) ^ nn_swz(kr);
         const int q = t.q0 + kr, n = col0 + c * 8;
         if (q < r && n < N) p = reinterpret_cast<const char*>(Rk + (size_t)q * N + n);
       } else {
@@ -327,69 +328,79 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       load_lds_16B(p, sb + w * 1024);
     }
   };
-  auto issue_ctx_one = [&](const LoadCtx& lc, int idx, char* sa, char* sb) {
-    if (lc.lora)
-      issue_lora_one(lc.lt, idx, sa, sb);
-    else
-      issue_one(lc.atile, lc.btile, idx, sa, sb);
-  };
 
-  // Which of the wave's FM fragments take part in a tile: all of them in a base tile, the
-  // fragments of task k in a LoRA tile of task k (the others' MFMAs are skipped).
+  // Which of the wave's WM / 32 pieces take part in a tile: all of them in a base tile, the
+  // pieces of task k in a LoRA tile of task k (the others' MFMAs are skipped).
   struct FragOn {
-    bool on[FM];
+    bool on[WM / 32];
   };
   auto frags_of = [&](int k) {  // k < 0: base tile
     FragOn f;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) f.on[i] = k < 0 || frag_task(wm * FM + i) == k;
+    for (int i = 0; i < WM / 32; ++i) f.on[i] = k < 0 || frag_task(wm * (WM / 32) + i) == k;
     return f;
   };
 
-  // one MFMA step on fragment set `cur`; behind MFMA number m: fragment reads 2m, 2m+1 of the
-  // next step into set `cur ^ 1` (if rd), and, in the last PER_TILE slots, one load of the tile
-  // `lc` describes (if ld).  `rd` and `ld` are std::true_type / std::false_type in the steady-state
-  // loop, so that it compiles to straight-line code (a conditional branch per slot costs the wave
-  // more than the slot's memory instruction), and plain bools in the few tiles around it; `fo` is
-  // std::true_type there (base tiles: every fragment) and a FragOn in the tiles around it.
-  auto step = [&](int cur, auto rd, const char* rsa, const char* rsb, int rks, auto ld, const LoadCtx& lc, char* lsa,
-                  char* lsb, const auto& fo) {
+  // Sub-step S (0..3) of a tile: the MFMAs of (half q = S / 2 of the contraction tile, half
+  // h = S % 2 of the wave's rows), weight fragment by weight fragment (MFMA number m uses weight
+  // fragment m / HM and row fragment m % HM of set h).  Row fragments are double-buffered: the HM
+  // fragments of the next sub-step are read behind the first HM MFMAs.  Weight fragments are
+  // not: they serve both sub-steps of a half tile, and in the second of them (h = 1) fragment j
+  // is re-read for the next half tile right behind its last MFMA (slot HM j + HM - 1), a whole
+  // sub-step before its next use -- 16 registers instead of 32.  The reads come from (rsa, rsb)
+  // (if rd); in sub-step 3, after the barrier, the remaining slots carry the PER_TILE loads of
+  // the tile `lc` into (lsa, lsb) (if ld).  rd and ld are std::true_type / std::false_type in
+  // the steady-state loop, so that it compiles to straight-line code, and plain bools in the few
+  // tiles around it; `fo` is std::true_type there (base tiles: every piece) and a FragOn in
+  // the tiles that may be LoRA tiles.
+  auto substep = [&](auto S_, auto rd, const char* rsa, const char* rsb, auto ld, const LoadCtx& lc, char* lsa, char* lsb,
+                     const auto& fo) {
+    constexpr int S = decltype(S_)::value;
+    constexpr int q = S / 2, h = S % 2;
+    constexpr int NS_ = (S + 1) % 4;                 // the sub-step whose row fragments are read now
+    constexpr int nq = NS_ / 2, nh = NS_ % 2;
+    static_assert((FN - 1) * (HM - 1) >= PER_TILE, "load slots");
 #pragma unroll
     for (int m = 0; m < NMF; ++m) {
-      const int i = m / FN, j = m % FN;
+      const int j = m / HM, i = m % HM;
       bool on = true;
-      if constexpr (!std::is_same_v<std::decay_t<decltype(fo)>, std::true_type>) on = fo.on[i];
-      if (on) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
-      if (rd && m < RSLOTS) {
-        read_op(rsa, rsb, rks, 2 * m, af[cur ^ 1], bfr[cur ^ 1]);
-        if (2 * m + 1 < NOPS) read_op(rsa, rsb, rks, 2 * m + 1, af[cur ^ 1], bfr[cur ^ 1]);
+      if constexpr (!std::is_same_v<std::decay_t<decltype(fo)>, std::true_type>) on = fo.on[(h * HM + i) / 2];
+      if (on) mfma_16x16x32(acc[h * HM + i][j], bfr[j], af[h][i]);
+      if (rd && m < HM) read_a(rsa, nq, nh, m, af[nh]);
+      if (rd && h == 1 && i == HM - 1) read_b(rsb, nq, j);
+      if (S == 3 && m >= HM && i != HM - 1) {
+        const int idx = (j - 1) * (HM - 1) + i;
+        if (ld && idx < PER_TILE) issue_one(lc, idx, lsa, lsb);
       }
-      if (ld && m >= NMF - PER_TILE) issue_ctx_one(lc, m - (NMF - PER_TILE), lsa, lsb);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
+  constexpr std::integral_constant<int, 0> S0{};
+  constexpr std::integral_constant<int, 1> S1{};
+  constexpr std::integral_constant<int, 2> S2{};
+  constexpr std::integral_constant<int, 3> S3{};
   const LoadCtx none{false, nullptr, nullptr, LoraTile{0, -1, 0}};
 
-  // the tile in stage s: steps 0..2, barrier, step 3 with the reads of the next tile's step 0
-  // (if rd) and the loads of the tile after that, `lc`, into stage s (if ld); `fo` as in step()
+  // the tile in stage s: sub-steps 0..2, barrier, sub-step 3 with the reads of the next tile's
+  // first fragments (if rd) and the loads of the tile after that, `lc`, into stage s (if ld)
   auto tile = [&](auto stage, auto rd, auto ld, const LoadCtx& lc, const auto& fo) {
     constexpr int s = decltype(stage)::value;
-    step(0, yes, sA[s], sB[s], 1, no, none, nullptr, nullptr, fo);
-    step(1, yes, sA[s], sB[s], 2, no, none, nullptr, nullptr, fo);
-    step(0, yes, sA[s], sB[s], 3, no, none, nullptr, nullptr, fo);
+    substep(S0, yes, sA[s], sB[s], no, none, nullptr, nullptr, fo);
+    substep(S1, yes, sA[s], sB[s], no, none, nullptr, nullptr, fo);
+    substep(S2, yes, sA[s], sB[s], no, none, nullptr, nullptr, fo);
     // the next tile has landed (this wave's part), every fragment of this tile is in registers
+    // (the weight fragments of this half tile stay in use until sub-step 3 re-reads them)
     wait_vmcnt<0>();
     wait_lds();
     __builtin_amdgcn_s_barrier();
-    step(1, rd, sA[s ^ 1], sB[s ^ 1], 0, ld, lc, sA[s], sB[s], fo);
+    substep(S3, rd, sA[s ^ 1], sB[s ^ 1], ld, lc, sA[s], sB[s], fo);
   };
   constexpr std::integral_constant<int, 0> stage0{};
   constexpr std::integral_constant<int, 1> stage1{};
 
-  // ---- main contraction loop (unrolled by the two stages so that stage addresses are constants)
-  static_assert(NS == 2 && KS == 4, "loop below is written for a double buffer of 4-step tiles");
+  // ---- main contraction loop (unrolled by the two stages so that stage addresses are constants).
   // Operand pairs run one after the other.  When a pair's last tile has passed its barrier every
   // wave holds that tile's last fragments in registers, so both stages are free for the next
   // pair's first two tiles.
@@ -403,7 +414,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     };
     auto issue_whole = [&](const LoadCtx& lc, char* sa, char* sb) {
 #pragma unroll
-      for (int idx = 0; idx < PER_TILE; ++idx) issue_ctx_one(lc, idx, sa, sb);
+      for (int idx = 0; idx < PER_TILE; ++idx) issue_one(lc, idx, sa, sb);
     };
     issue_whole(base_ctx(0), sA[0], sB[0]);
     if (VT > 1) {
@@ -414,7 +425,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     }
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int op = 0; op < NOPS; ++op) read_op(sA[0], sB[0], 0, op, af[0], bfr[0]);
+    for (int j = 0; j < FN; ++j) read_b(sB[0], 0, j);
+#pragma unroll
+    for (int i = 0; i < HM; ++i) read_a(sA[0], 0, 0, i, af[0]);
     __builtin_amdgcn_sched_barrier(0);
     // steady state, two base tiles per trip: both have a successor to read and a base tile to load
     int v = 0;
@@ -447,24 +460,23 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   if (wave / WPA == 2) ep = sB0;
   if (wave / WPA == 3) ep = sB1;
   ep += (wave % WPA) * WBYTES;
+  // lane 16 kg + r16 holds row 16 i + r16, columns 16 j + 4 kg + 0..3 of the wave's sub-tile
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
+    for (int j = 0; j < FN; ++j) {
+      bf16x4 o;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16>(acc[i][j][4 * g + e]);
-        const int m = 32 * i + l32, c = 4 * j + g;
-        *(bf16x4*)(ep + m * OROWB + ((c ^ oswz(m)) << 4) + 8 * lhi) = o;
-      }
+      for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16>(acc[i][j][e]);
+      const int m = 16 * i + r16, c = 2 * j + (kg >> 1);
+      *(bf16x4*)(ep + m * OROWB + ((c ^ oswz(m)) << 4) + 8 * (kg & 1)) = o;
+    }
 #pragma unroll
   for (int it = 0; it < WM / ORPI; ++it) {
     const int r = ORPI * it + lane / OCH, cp = lane % OCH;
     const int c = cp ^ oswz(r);
     const uint4 v = *(const uint4*)(ep + r * OROWB + cp * 16);
-    const int f = (wm * WM + r) >> 5, o = r & 31;  // the row's fragment of the block (WM is a multiple of 32)
+    const int f = (wm * WM + r) >> 5, o = r & 31;  // the row's piece of the block (WM is a multiple of 32)
     const int grow = s_frow[f] + o, gcol = col0 + wn * WN + c * 8;
     // non-temporal: the output is not read again by this launch, so it should not displace the
     // operand strips in the L2 / Infinity Cache (measured +0.7 % on the whole forward + backward)

@@ -32,13 +32,6 @@ __device__ __forceinline__ void load_lds_16B_sbase(const void* base_uniform, uns
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base_uniform), "s"(lds)
                : "memory", "m0");
 }
-// Direct global->LDS load of 4 B per lane (lane l's data lands at lds_wave_base + 4 l), used to
-// pull cache lines into the L2 ahead of time: the destination is a scratch area nobody reads.
-__device__ __forceinline__ void load_lds_4B_sbase(const void* base_uniform, unsigned lane_off, char* lds_wave_base) {
-  const unsigned lds = (unsigned)(size_t)(MLORA_AS3 char*)lds_wave_base;
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(lane_off), "s"(base_uniform), "s"(lds)
-               : "memory", "m0");
-}
 #pragma clang diagnostic pop
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {

@@ -239,9 +239,6 @@ mlora_status validate_group(const mlora_problem* const* ps, int P) {
 }
 
 }  // namespace
-
-int kernel_path_flags() { return g_kernel_path.load(); }
-
 }  // namespace mlora
 
 using namespace mlora;

@@ -79,9 +79,6 @@ hipError_t generic_gemm_bwd(const CallCtx& c, const void* dY, void* dX, const vo
 hipError_t generic_dB(const CallCtx& c, const void* Z, const void* dY, const OutTable& dB, int accumulate);
 hipError_t generic_dA(const CallCtx& c, const void* X, const void* G, const OutTable& dA, int accumulate);
 
-// mlora_api.hip : the process-wide test switch (mlora_set_kernel_path)
-int kernel_path_flags();
-
 // gemm_mfma.hip : bf16 MFMA GEMM with the LoRA term as extra contraction steps
 bool gemm_mfma_ok(int M, int N, int Kd);
 hipError_t gemm_mfma(const bf16* A, const bf16* Bm, bf16* C, int M, int N, int Kd, bool nn, const bf16* L, int ldz,
