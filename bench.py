@@ -9,8 +9,9 @@ resident in HBM before the timed region starts.
 
 Prints ONE JSON line:
   metric/value   useful TFLOP/s of the whole step (4 T h d + 6 sum t_k r_k (h+d) per projection)
-  roofline       the MFMA base-product kernel against the dense bf16 MFMA peak, timed with
-                 HIP events recorded by the library on the launch stream during the timed steps
+  roofline       the MFMA base-product kernel against the dense bf16 MFMA peak, from HIP events the
+                 library records on the launch stream around each of its launches, in a pass of
+                 its own after the timed region (the timed steps run without those events)
   roofline_lowrank  the same for the four HBM-bound low-rank kernels against the HBM peak
   cpu_baseline   the CPU fp64 oracle timed on this machine's host cores on a bounded token sample
 """
@@ -30,14 +31,17 @@ WORKLOAD = "llama2_13b_layer"
 
 
 def _traffic_bytes_per_launch():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
-    (profiles/gemm_traffic.json), or None if that summary is absent."""
+    """Bytes per launch that the dominant kernel's L2 misses request from the memory side
+    (FETCH_SIZE + WRITE_SIZE), from the committed rocprofv3 counter runs of this same command
+    (profiles/gemm_traffic.json); (None, None) if that summary is absent.  Counters cannot be read
+    inside this process, so the figure belongs to the kernel build the summary names."""
     p = os.path.join(ROOT, "profiles", "gemm_traffic.json")
     try:
         with open(p) as f:
-            return json.load(f).get("hbm_bytes_per_launch_avg")
+            d = json.load(f)
+            return d.get("hbm_bytes_per_launch_avg"), d.get("source")
     except (OSError, ValueError):
-        return None
+        return None, None
 
 
 def sample_power(run_steps, seconds=2.0):
@@ -109,6 +113,7 @@ def cpu_baseline(wl_mod, w, tokens_per_adapter, seed):
         total_s += time.perf_counter() - t0
         total_flops += orc.flops(Ts, p.h, p.d, off, w.ranks)
     return {"value": total_flops / total_s / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "implementation": "numpy float64; every product of the equations is one multithreaded BLAS dgemm",
             "tokens_per_s": Ts / total_s, "seconds": total_s,
             "sample": f"first {tokens_per_adapter} tokens of each of the {K} adapters ({Ts} of {w.T} tokens), "
                       f"all 7 projections, fp64 forward+backward"}
@@ -182,12 +187,17 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    mb.profile_kernels(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # per-kernel durations: the same steps once more, each launch bracketed by HIP events
+    prof_steps = min(args.steps, 5)
+    mb.profile_kernels(True)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
     mb.profile_kernels(False)
     prof = mb.profile_kernels_read()
     gemm_ms, gemm_flops, gemm_launches = prof["gemm"]
@@ -195,6 +205,7 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    traffic, traffic_src = _traffic_bytes_per_launch()
     out = {
         "metric": "multi-adapter LoRA linear fwd+bwd TFLOP/s",
         "value": tflops, "unit": "TFLOP/s",
@@ -209,15 +220,15 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "k_gemm_mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "launches": gemm_launches, "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
-                     "share_of_step_time": gemm_ms / args.steps / ms_per_step,
-                     "traffic": _traffic_bytes_per_launch()},
+                     "share_of_step_time": gemm_ms / prof_steps / ms_per_step,
+                     "traffic": traffic, "traffic_source": traffic_src},
     }
     # the HBM-bound kernels (s x A and s dy B^T: "rows"; dA_k and dB_k: "grad"): algorithmic bytes per
     # launch (activations read once, results written once) over the HIP-event duration
     out["roofline_lowrank"] = {
         kind: {"bound": "hbm", "kernel": kname, "achieved": (by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0),
                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": (by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS if ms > 0 else 0.0),
-               "launches": n, "avg_launch_ms": ms / max(n, 1), "share_of_step_time": ms / args.steps / ms_per_step}
+               "launches": n, "avg_launch_ms": ms / max(n, 1), "share_of_step_time": ms / prof_steps / ms_per_step}
         for kind, kname, (ms, by, n) in (("rows", "k_lowrank_mfma", prof["rows"]), ("grad", "k_grad_mfma", prof["grad"]))}
     if not args.no_power:
         out["power"] = sample_power(step)

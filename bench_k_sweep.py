@@ -31,7 +31,9 @@ def main():
     ap.add_argument("--iters", type=int, default=15)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--md", action="store_true", help="print a markdown table instead of JSON lines")
     args = ap.parse_args()
+    rows = []
 
     import torch
     from paper_2312_02515_amd import binding as mb
@@ -84,11 +86,19 @@ def main():
 
             tb, ts = timed(batched), timed(separate)
             flops = 4.0 * T * h * d + 6.0 * T * args.rank * (h + d)
-            print(json.dumps({"T": T, "K": K, "tokens_per_task": t, "h": h, "d": d, "rank": args.rank,
-                              "batched_ms": tb, "separate_ms": ts, "separate_over_batched": ts / tb,
-                              "batched_tflops": flops / tb / 1e9, "separate_tflops": flops / ts / 1e9,
-                              "launches_batched": 6, "launches_separate": 6 * K}), flush=True)
+            rec = {"T": T, "K": K, "tokens_per_task": t, "h": h, "d": d, "rank": args.rank,
+                   "batched_ms": tb, "separate_ms": ts, "separate_over_batched": ts / tb,
+                   "batched_tflops": flops / tb / 1e9, "separate_tflops": flops / ts / 1e9}
+            rows.append(rec)
+            if not args.md:
+                print(json.dumps(rec), flush=True)
             del inp, Y, dX, whole, saved, ws, dA, dB, parts
+    if args.md:
+        print("| T | K | tokens per task | batched ms | separate ms | separate / batched | batched TFLOP/s |")
+        print("|---|---|---|---|---|---|---|")
+        for r in rows:
+            print(f'| {r["T"]} | {r["K"]} | {r["tokens_per_task"]} | {r["batched_ms"]:.3f} | {r["separate_ms"]:.3f} '
+                  f'| {r["separate_over_batched"]:.2f} | {r["batched_tflops"]:.0f} |')
 
 
 if __name__ == "__main__":
