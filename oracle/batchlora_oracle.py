@@ -180,9 +180,11 @@ def gather_rows_problem(rows, seg_offsets, T):
     too slow for.  Every row of H and of dX depends on its own row of X / dH
     only, so the rows `rows` (sorted, unique) of the full problem equal the
     output of the smaller problem made of just those rows, with the segment
-    offsets recomputed.  Returns (rows_sorted, new_offsets, lead, tail) where
-    the gathered matrix is [lead uncovered rows | rows of task 0 | ... | tail
-    uncovered rows] -- which is the sorted order already.
+    offsets recomputed.  Returns (rows_sorted, new_offsets): the gathered
+    matrix takes the rows in sorted order, which already is [uncovered rows
+    before the first task | rows of task 0 | ... | uncovered rows after the
+    last task], and new_offsets[k] is the position of the first gathered row
+    that is >= seg_offsets[k].
     """
     rows = np.unique(np.asarray(rows, dtype=np.int64))
     assert rows.size == 0 or (rows[0] >= 0 and rows[-1] < T)
