@@ -130,6 +130,9 @@ def main():
     ap.add_argument("--recompute", action="store_true",
                     help="time the activation-recompute pair of entry points (nothing saved between forward and "
                          "backward; the backward recomputes s x A) instead of the default pair")
+    ap.add_argument("--w8", action="store_true",
+                    help="time the 8-bit-weight pair of entry points (the frozen weight is handed over as int8 "
+                         "codes + per-column scales and decoded inside every call) instead of the default pair")
     ap.add_argument("--kernel-path", type=int, default=0,
                     help="test switch of include/mlora_testing.h (bit mask; 0 = the fastest kernels)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -158,8 +161,16 @@ def main():
         inp = wl.make_workload_inputs(w, pi, device=dev, seed=args.seed)
         prob = mb.Problem(w.T, p.h, p.d, inp.W, inp.seg_offsets, inp.ranks, inp.scalings, inp.A, inp.B)
         dA, dB = prob.alloc_grads()
-        projs.append(dict(p=p, inp=inp, prob=prob, saved=prob.alloc_saved(),
-                          ws=prob.alloc_recompute_workspace() if args.recompute else prob.alloc_workspace(),
+        if args.w8:
+            Wq, c = mb.mlora_w8_quantize(inp.W)
+            torch.cuda.synchronize()
+            inp.W = None                   # the bf16 weight is gone: only its code stays resident
+            prob = mb.Problem(w.T, p.h, p.d, None, inp.seg_offsets, inp.ranks, inp.scalings, inp.A, inp.B,
+                              dtype=inp.X.dtype, device=dev)
+        projs.append(dict(p=p, inp=inp, prob=prob, saved=prob.alloc_saved(), Wq=Wq if args.w8 else None,
+                          c=c if args.w8 else None,
+                          ws=prob.alloc_w8_workspace() if args.w8 else
+                          prob.alloc_recompute_workspace() if args.recompute else prob.alloc_workspace(),
                           Y=torch.empty((w.T, p.d), dtype=inp.X.dtype, device=dev),
                           dX=torch.empty((w.T, p.h), dtype=inp.X.dtype, device=dev), dA=dA, dB=dB))
     flops_step = sum(w.flops(p) for p in w.projections)
@@ -171,6 +182,13 @@ def main():
             for q in reversed(projs):
                 mb.mlora_lora_bwd_recompute(q["prob"], q["inp"].X, q["inp"].dY, q["dX"], q["dA"], q["dB"], False,
                                             q["ws"], stream)
+            return
+        if args.w8:
+            for q in projs:
+                mb.mlora_lora_fwd_w8(q["prob"], q["Wq"], q["c"], q["inp"].X, q["Y"], q["saved"], q["ws"], stream)
+            for q in reversed(projs):
+                mb.mlora_lora_bwd_w8(q["prob"], q["Wq"], q["c"], q["inp"].X, q["inp"].dY, q["saved"], q["dX"],
+                                     q["dA"], q["dB"], False, q["ws"], stream)
             return
         for q in projs:
             mb.mlora_lora_fwd(q["prob"], q["inp"].X, q["Y"], q["saved"], q["ws"], stream)
@@ -214,7 +232,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD, "tokens": w.T, "adapters": w.K, "ranks": list(w.ranks),
                    "projections": [f"{p.name}:{p.h}x{p.d}" for p in w.projections], "seed": args.seed,
-                   "variant": "recompute" if args.recompute else "saved"},
+                   "variant": "w8" if args.w8 else "recompute" if args.recompute else "saved"},
         "tokens_per_s": w.T / (ms_per_step * 1e-3),
         "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "k_gemm_mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,

@@ -89,7 +89,8 @@ typedef struct {
 /* Size in bytes of the `saved` buffer that mlora_lora_fwd fills and mlora_lora_bwd reads
  * (the intermediate s_k x_k A_k of the forward workflow, section 3.3.1, kept so that the
  * backward pass does not recompute it).  Its layout is private to the library.
- * Returns 0 if the problem is invalid. */
+ * Returns 0 if the problem is invalid; p->W is not looked at (it may be NULL, as in the
+ * problems of the 8-bit-weight calls below). */
 size_t mlora_lora_saved_bytes(const mlora_problem* p);
 
 /* Size in bytes of the scratch `workspace` either call needs (the larger of the two).
@@ -184,6 +185,45 @@ mlora_status mlora_lora_group_bwd(const mlora_problem* const* ps, int P, const v
                                   const void* const* dY, const void* const* saved, void* dX,
                                   float* const* const* dA, float* const* const* dB, int accumulate,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- 8-bit frozen base weight ------------------------------------------------------------
+ * The single-GPU setup of section 4.1 keeps the frozen pre-trained weights in 8 bits.  The
+ * paper names the technique without a format; this library's reading is the weight-only,
+ * column-wise absmax code (one fp32 scale per output feature):
+ *     c[j]     = max_i |W[i,j]| / 127                  fp32 division
+ *     Wq[i,j]  = rint( W[i,j] / c[j] )  in [-127,127]   fp32 division, halves to even;
+ *                                                       0 where c[j] = 0
+ *     W^[i,j]  = Wq[i,j] * c[j]
+ * and W^ takes the place of W in Eq. "forward" and Eq. "grad_output" (Eq. "grad_lora" does not
+ * contain W).  Activations, adapters, gradients and all products keep the problem's dtype; the
+ * kernels read W^ in that dtype: the fp32 product Wq[i,j] * c[j], rounded to the nearest-even
+ * bfloat16 for MLORA_BF16.  W must be finite.
+ *   Wq   DEVICE int8  [h, d], row-major like W
+ *   c    DEVICE float [d]
+ *
+ * mlora_w8_quantize: codes W (DEVICE [h, d] of `dtype`, read only) into Wq and c (outputs).
+ * mlora_w8_dequantize: writes W^ into W_hat (DEVICE [h, d] of `dtype`, output).
+ * Both: MLORA_ERR_NULL / MLORA_ERR_DTYPE / MLORA_ERR_SHAPE (h or d not in [1, 2^22]).
+ *
+ * mlora_lora_fwd_w8 / mlora_lora_bwd_w8: mlora_lora_fwd / mlora_lora_bwd with the weight given
+ * as (Wq, c); p->W is ignored (may be NULL).  Each call first decodes W^ into its workspace
+ * (one streaming pass, 1 byte read and one element written per weight) and then runs the same
+ * kernels as the plain calls, so its results are bit-identical to the plain calls on
+ * mlora_w8_dequantize's output; nothing decoded is kept between calls (a backward call with
+ * dX == NULL decodes nothing).  `saved` is interchangeable with the plain calls' (it does not
+ * depend on W).  The workspace must hold mlora_lora_w8_workspace_bytes(p) bytes (the plain
+ * workspace plus h * d elements; 0 if the problem is invalid), 256-byte aligned.  Errors as for
+ * the plain calls, MLORA_ERR_NULL also for a NULL Wq or c. */
+mlora_status mlora_w8_quantize(const void* W, int32_t dtype, int64_t h, int64_t d, int8_t* Wq, float* c,
+                               void* hip_stream);
+mlora_status mlora_w8_dequantize(const int8_t* Wq, const float* c, int32_t dtype, int64_t h, int64_t d,
+                                 void* W_hat, void* hip_stream);
+size_t mlora_lora_w8_workspace_bytes(const mlora_problem* p);
+mlora_status mlora_lora_fwd_w8(const mlora_problem* p, const int8_t* Wq, const float* c, const void* X, void* Y,
+                               void* saved, void* workspace, size_t workspace_bytes, void* hip_stream);
+mlora_status mlora_lora_bwd_w8(const mlora_problem* p, const int8_t* Wq, const float* c, const void* X,
+                               const void* dY, const void* saved, void* dX, float* const* dA, float* const* dB,
+                               int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Plain text for a status code; never NULL. */
 const char* mlora_status_string(mlora_status s);

@@ -28,7 +28,8 @@ EXPORTS = ["mlora_lora_saved_bytes", "mlora_lora_workspace_bytes", "mlora_lora_v
            "mlora_lora_bwd", "mlora_lora_recompute_workspace_bytes", "mlora_lora_fwd_nosave",
            "mlora_lora_bwd_recompute", "mlora_lora_group_validate", "mlora_lora_group_workspace_bytes",
            "mlora_lora_group_fwd", "mlora_lora_group_bwd", "mlora_status_string", "mlora_last_hip_error",
-           "mlora_lora_kernel_path", "mlora_lora_bwd_static"]
+           "mlora_lora_kernel_path", "mlora_lora_bwd_static", "mlora_w8_quantize", "mlora_w8_dequantize",
+           "mlora_lora_w8_workspace_bytes", "mlora_lora_fwd_w8", "mlora_lora_bwd_w8"]
 MLORA_STATIC_SCRATCH_BYTES = 32 << 20
 # include/mlora_testing.h: test and measurement switches
 TESTING_EXPORTS = ["mlora_set_kernel_path", "mlora_profile_kernels", "mlora_profile_kernels_read"]
@@ -78,6 +79,22 @@ def _load() -> ctypes.CDLL:
                                         ctypes.c_void_p]
     l.mlora_lora_recompute_workspace_bytes.restype = ctypes.c_size_t
     l.mlora_lora_recompute_workspace_bytes.argtypes = [pp]
+    l.mlora_w8_quantize.restype = ctypes.c_int
+    l.mlora_w8_quantize.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p]
+    l.mlora_w8_dequantize.restype = ctypes.c_int
+    l.mlora_w8_dequantize.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_void_p, ctypes.c_void_p]
+    l.mlora_lora_w8_workspace_bytes.restype = ctypes.c_size_t
+    l.mlora_lora_w8_workspace_bytes.argtypes = [pp]
+    l.mlora_lora_fwd_w8.restype = ctypes.c_int
+    l.mlora_lora_fwd_w8.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    l.mlora_lora_bwd_w8.restype = ctypes.c_int
+    l.mlora_lora_bwd_w8.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
+                                    ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                    ctypes.c_void_p]
     l.mlora_lora_fwd_nosave.restype = ctypes.c_int
     l.mlora_lora_fwd_nosave.argtypes = [pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                         ctypes.c_void_p]
@@ -127,27 +144,30 @@ def _dtype_code(dt: torch.dtype) -> int:
 
 class Problem:
     """Host-side description of one call: owns the ctypes arrays the struct points to
-    and keeps the adapter tensors alive."""
+    and keeps the adapter tensors alive.  W may be None for the calls that take the weight in
+    its 8-bit code (then `dtype` and `device` say what W would have been)."""
 
-    def __init__(self, T: int, h: int, d: int, W: torch.Tensor, seg_offsets: Sequence[int], ranks: Sequence[int],
-                 scalings: Sequence[float], A: Sequence[torch.Tensor], B: Sequence[torch.Tensor]):
+    def __init__(self, T: int, h: int, d: int, W: Optional[torch.Tensor], seg_offsets: Sequence[int],
+                 ranks: Sequence[int], scalings: Sequence[float], A: Sequence[torch.Tensor], B: Sequence[torch.Tensor],
+                 dtype: Optional[torch.dtype] = None, device=None):
         K = len(ranks)
         self.T, self.h, self.d, self.K = int(T), int(h), int(d), K
         self.ranks = [int(r) for r in ranks]
         self.W, self.A, self.B = W, list(A), list(B)
-        self.torch_dtype = W.dtype
+        self.torch_dtype = W.dtype if W is not None else dtype
+        self.device = W.device if W is not None else torch.device(device)
         self._off = (ctypes.c_int64 * (K + 1))(*[int(o) for o in seg_offsets])
         self._ranks = (ctypes.c_int32 * max(K, 1))(*self.ranks)
         self._s = (ctypes.c_float * max(K, 1))(*[float(s) for s in scalings])
         self._A = (ctypes.c_void_p * max(K, 1))(*[a.data_ptr() for a in A])
         self._B = (ctypes.c_void_p * max(K, 1))(*[b.data_ptr() for b in B])
-        self.c = mlora_problem(T=self.T, h=self.h, d=self.d, K=K, dtype=_dtype_code(W.dtype),
+        self.c = mlora_problem(T=self.T, h=self.h, d=self.d, K=K, dtype=_dtype_code(self.torch_dtype),
                                seg_offsets=ctypes.cast(self._off, ctypes.POINTER(ctypes.c_int64)),
                                ranks=ctypes.cast(self._ranks, ctypes.POINTER(ctypes.c_int32)),
                                scalings=ctypes.cast(self._s, ctypes.POINTER(ctypes.c_float)),
                                A=ctypes.cast(self._A, ctypes.POINTER(ctypes.c_void_p)),
                                B=ctypes.cast(self._B, ctypes.POINTER(ctypes.c_void_p)),
-                               W=W.data_ptr())
+                               W=W.data_ptr() if W is not None else None)
 
     def saved_bytes(self) -> int:
         return int(lib.mlora_lora_saved_bytes(ctypes.byref(self.c)))
@@ -159,7 +179,7 @@ class Problem:
         return int(lib.mlora_lora_recompute_workspace_bytes(ctypes.byref(self.c)))
 
     def alloc_recompute_workspace(self) -> torch.Tensor:
-        return torch.empty(self.recompute_workspace_bytes(), dtype=torch.uint8, device=self.W.device)
+        return torch.empty(self.recompute_workspace_bytes(), dtype=torch.uint8, device=self.device)
 
     def validate(self) -> int:
         return int(lib.mlora_lora_validate(ctypes.byref(self.c)))
@@ -169,14 +189,20 @@ class Problem:
         return int(lib.mlora_lora_kernel_path(ctypes.byref(self.c)))
 
     def alloc_saved(self) -> torch.Tensor:
-        return torch.empty(self.saved_bytes(), dtype=torch.uint8, device=self.W.device)
+        return torch.empty(self.saved_bytes(), dtype=torch.uint8, device=self.device)
 
     def alloc_workspace(self) -> torch.Tensor:
-        return torch.empty(self.workspace_bytes(), dtype=torch.uint8, device=self.W.device)
+        return torch.empty(self.workspace_bytes(), dtype=torch.uint8, device=self.device)
+
+    def w8_workspace_bytes(self) -> int:
+        return int(lib.mlora_lora_w8_workspace_bytes(ctypes.byref(self.c)))
+
+    def alloc_w8_workspace(self) -> torch.Tensor:
+        return torch.empty(self.w8_workspace_bytes(), dtype=torch.uint8, device=self.device)
 
     def alloc_grads(self):
-        dA = [torch.empty((self.h, r), dtype=torch.float32, device=self.W.device) for r in self.ranks]
-        dB = [torch.empty((r, self.d), dtype=torch.float32, device=self.W.device) for r in self.ranks]
+        dA = [torch.empty((self.h, r), dtype=torch.float32, device=self.device) for r in self.ranks]
+        dB = [torch.empty((r, self.d), dtype=torch.float32, device=self.device) for r in self.ranks]
         return dA, dB
 
 
@@ -228,6 +254,58 @@ def mlora_lora_bwd_static(prob: Problem, X: torch.Tensor, dY: torch.Tensor, save
         raise MloraError(st, "mlora_lora_bwd_static")
 
 
+def mlora_w8_quantize(W: torch.Tensor, stream: Optional[torch.cuda.Stream] = None):
+    """Column-wise absmax code of W [h, d]: returns (Wq int8 [h, d], c float32 [d])."""
+    h, d = W.shape
+    Wq = torch.empty((h, d), dtype=torch.int8, device=W.device)
+    c = torch.empty((d,), dtype=torch.float32, device=W.device)
+    st = lib.mlora_w8_quantize(W.data_ptr(), _dtype_code(W.dtype), h, d, Wq.data_ptr(), c.data_ptr(),
+                               _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_w8_quantize")
+    return Wq, c
+
+
+def mlora_w8_dequantize(Wq: torch.Tensor, c: torch.Tensor, dtype: torch.dtype,
+                        stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """W^ = Wq c_j in the storage type `dtype`."""
+    h, d = Wq.shape
+    out = torch.empty((h, d), dtype=dtype, device=Wq.device)
+    st = lib.mlora_w8_dequantize(Wq.data_ptr(), c.data_ptr(), _dtype_code(dtype), h, d, out.data_ptr(),
+                                 _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_w8_dequantize")
+    return out
+
+
+def mlora_lora_fwd_w8(prob: Problem, Wq: torch.Tensor, c: torch.Tensor, X: torch.Tensor, Y: torch.Tensor,
+                      saved: torch.Tensor, workspace: torch.Tensor,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+    """mlora_lora_fwd with the frozen weight given as its 8-bit code (Wq, c)."""
+    st = lib.mlora_lora_fwd_w8(ctypes.byref(prob.c), Wq.data_ptr(), c.data_ptr(), X.data_ptr(), Y.data_ptr(),
+                               saved.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                               _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_fwd_w8")
+
+
+def mlora_lora_bwd_w8(prob: Problem, Wq: torch.Tensor, c: torch.Tensor, X: torch.Tensor, dY: torch.Tensor,
+                      saved: torch.Tensor, dX: Optional[torch.Tensor], dA: List[torch.Tensor], dB: List[torch.Tensor],
+                      accumulate: bool, workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """mlora_lora_bwd with the frozen weight given as its 8-bit code (Wq, c)."""
+    K = prob.K
+    pa = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dA])
+    pb = (ctypes.c_void_p * max(K, 1))(*[t.data_ptr() for t in dB])
+    st = lib.mlora_lora_bwd_w8(ctypes.byref(prob.c), Wq.data_ptr(), c.data_ptr(), X.data_ptr(), dY.data_ptr(),
+                               saved.data_ptr(), dX.data_ptr() if dX is not None else None,
+                               ctypes.cast(pa, ctypes.POINTER(ctypes.c_void_p)),
+                               ctypes.cast(pb, ctypes.POINTER(ctypes.c_void_p)), 1 if accumulate else 0,
+                               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                               _stream_handle(stream))
+    if st != 0:
+        raise MloraError(st, "mlora_lora_bwd_w8")
+
+
 def mlora_lora_fwd_nosave(prob: Problem, X: torch.Tensor, Y: torch.Tensor, workspace: torch.Tensor,
                           stream: Optional[torch.cuda.Stream] = None) -> None:
     """Forward of the activation-recompute variant: as mlora_lora_fwd, nothing saved."""
@@ -270,7 +348,7 @@ class Group:
         return int(lib.mlora_lora_group_workspace_bytes(self.c, self.P))
 
     def alloc_workspace(self) -> torch.Tensor:
-        return torch.empty(self.workspace_bytes(), dtype=torch.uint8, device=self.problems[0].W.device)
+        return torch.empty(self.workspace_bytes(), dtype=torch.uint8, device=self.problems[0].device)
 
 
 def _ptr_array(tensors):

@@ -40,7 +40,8 @@ hipError_t static_scratch(void** out) {
 thread_local int g_last_hip_error = 0;
 std::atomic<int> g_kernel_path{0};
 
-mlora_status validate(const mlora_problem* p) {
+// `need_W` = false: for the queries and calls that never read p->W
+mlora_status validate(const mlora_problem* p, bool need_W = true) {
   if (p == nullptr) return MLORA_ERR_NULL;
   if (p->dtype != MLORA_BF16 && p->dtype != MLORA_F32) return MLORA_ERR_DTYPE;
   if (p->T < 0 || p->h <= 0 || p->d <= 0) return MLORA_ERR_SHAPE;
@@ -52,7 +53,7 @@ mlora_status validate(const mlora_problem* p) {
     if ((p->T / 256 + 1) * (wide / 256 + 1) > 0x7fffffffLL) return MLORA_ERR_SHAPE;
   }
   if (p->K < 0 || p->K > kMaxK) return MLORA_ERR_SHAPE;
-  if (p->W == nullptr) return MLORA_ERR_NULL;
+  if (need_W && p->W == nullptr) return MLORA_ERR_NULL;
   if (p->K > 0) {
     if (!p->seg_offsets || !p->ranks || !p->scalings || !p->A || !p->B) return MLORA_ERR_NULL;
     int64_t prev = 0;
@@ -248,7 +249,7 @@ extern "C" {
 mlora_status mlora_lora_validate(const mlora_problem* p) { return validate(p); }
 
 size_t mlora_lora_saved_bytes(const mlora_problem* p) {
-  if (validate(p) != MLORA_OK) return 0;
+  if (validate(p, false) != MLORA_OK) return 0;
   size_t b = lowrank_bytes(p);
   return b ? b : 256;
 }
@@ -341,6 +342,91 @@ mlora_status mlora_lora_bwd_recompute(const mlora_problem* p, const void* X, con
   float* partial =
       grad_scratch_bytes(p) ? reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * lowrank_bytes(p)) : nullptr;
   return hip_status(backward_impl(p, c, X, dY, Z, workspace, dX, dA, dB, accumulate, partial));
+}
+
+// ---- 8-bit frozen base weight: decode into the head of the workspace, then the plain path ----
+namespace {
+
+size_t w8_weight_bytes(const mlora_problem* p) { return align_up((size_t)p->h * (size_t)p->d * elem_size(p), 256); }
+
+mlora_status w8_check_matrix(const void* a, const void* b, const void* c, int32_t dtype, int64_t h, int64_t d) {
+  if (a == nullptr || b == nullptr || c == nullptr) return MLORA_ERR_NULL;
+  if (dtype != MLORA_BF16 && dtype != MLORA_F32) return MLORA_ERR_DTYPE;
+  if (h < 1 || d < 1 || h > (1 << 22) || d > (1 << 22)) return MLORA_ERR_SHAPE;
+  return MLORA_OK;
+}
+
+// The problem as the plain entry points see it: W^ lives at the head of the workspace.
+// (validate() only asks that W is not NULL, so any non-NULL stand-in serves for the checks.)
+mlora_problem w8_plain_problem(const mlora_problem* p, const void* w_hat) {
+  mlora_problem q = *p;
+  q.W = w_hat;
+  return q;
+}
+
+}  // namespace
+
+mlora_status mlora_w8_quantize(const void* W, int32_t dtype, int64_t h, int64_t d, int8_t* Wq, float* c,
+                               void* hip_stream) {
+  const mlora_status st = w8_check_matrix(W, Wq, c, dtype, h, d);
+  if (st != MLORA_OK) return st;
+  return hip_status(w8_quantize(W, dtype, (int)h, (int)d, Wq, c, static_cast<hipStream_t>(hip_stream)));
+}
+
+mlora_status mlora_w8_dequantize(const int8_t* Wq, const float* c, int32_t dtype, int64_t h, int64_t d, void* W_hat,
+                                 void* hip_stream) {
+  const mlora_status st = w8_check_matrix(Wq, c, W_hat, dtype, h, d);
+  if (st != MLORA_OK) return st;
+  return hip_status(w8_dequantize(Wq, c, dtype, (int)h, (int)d, W_hat, static_cast<hipStream_t>(hip_stream)));
+}
+
+size_t mlora_lora_w8_workspace_bytes(const mlora_problem* p) {
+  if (p == nullptr) return 0;
+  static const char stand_in = 0;
+  const mlora_problem q = w8_plain_problem(p, &stand_in);
+  if (validate(&q) != MLORA_OK) return 0;
+  return w8_weight_bytes(&q) + mlora_lora_workspace_bytes(&q);
+}
+
+mlora_status mlora_lora_fwd_w8(const mlora_problem* p, const int8_t* Wq, const float* c, const void* X, void* Y,
+                               void* saved, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (p == nullptr) return MLORA_ERR_NULL;
+  static const char stand_in = 0;
+  mlora_problem q = w8_plain_problem(p, workspace ? workspace : &stand_in);
+  mlora_status st = validate(&q);
+  if (st != MLORA_OK) return st;
+  if (Wq == nullptr || c == nullptr) return MLORA_ERR_NULL;
+  if (q.T == 0) return MLORA_OK;
+  if (X == nullptr || Y == nullptr || saved == nullptr) return MLORA_ERR_NULL;
+  if (workspace == nullptr || workspace_bytes < mlora_lora_w8_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
+  const hipError_t e = w8_dequantize(Wq, c, q.dtype, (int)q.h, (int)q.d, workspace, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_status(e);
+  const size_t wb = w8_weight_bytes(&q);
+  return mlora_lora_fwd(&q, X, Y, saved, static_cast<char*>(workspace) + wb, workspace_bytes - wb, hip_stream);
+}
+
+mlora_status mlora_lora_bwd_w8(const mlora_problem* p, const int8_t* Wq, const float* c, const void* X,
+                               const void* dY, const void* saved, void* dX, float* const* dA, float* const* dB,
+                               int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (p == nullptr) return MLORA_ERR_NULL;
+  static const char stand_in = 0;
+  mlora_problem q = w8_plain_problem(p, workspace ? workspace : &stand_in);
+  mlora_status st = validate(&q);
+  if (st != MLORA_OK) return st;
+  if (Wq == nullptr || c == nullptr) return MLORA_ERR_NULL;
+  if (q.T > 0 && (X == nullptr || dY == nullptr || saved == nullptr)) return MLORA_ERR_NULL;
+  st = check_grad_tables(&q, dA, dB);
+  if (st != MLORA_OK) return st;
+  if (workspace == nullptr || workspace_bytes < mlora_lora_w8_workspace_bytes(p)) return MLORA_ERR_WORKSPACE;
+  if (q.T == 0 && accumulate) return MLORA_OK;
+  if (dX != nullptr && q.T > 0) {   // only the input gradient reads the weight
+    const hipError_t e =
+        w8_dequantize(Wq, c, q.dtype, (int)q.h, (int)q.d, workspace, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_status(e);
+  }
+  const size_t wb = w8_weight_bytes(&q);
+  return mlora_lora_bwd(&q, X, dY, saved, dX, dA, dB, accumulate, static_cast<char*>(workspace) + wb,
+                        workspace_bytes - wb, hip_stream);
 }
 
 mlora_status mlora_lora_group_validate(const mlora_problem* const* ps, int P) { return validate_group(ps, P); }

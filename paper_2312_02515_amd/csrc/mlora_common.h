@@ -104,6 +104,10 @@ int profile_begin(int kind, double units, hipStream_t stream);
 void profile_end(int slot, hipStream_t stream);
 hipError_t profile_read(double* ms, double* units, int* launches);
 
+// w8_kernels.hip : column-wise absmax code of the frozen weight and its decoder
+hipError_t w8_quantize(const void* W, int dtype, int h, int d, int8_t* Wq, float* c, hipStream_t stream);
+hipError_t w8_dequantize(const int8_t* Wq, const float* c, int dtype, int h, int d, void* Wh, hipStream_t stream);
+
 // lowrank_mfma.hip : bf16 MFMA kernels for Z, G (row-local) and dA_k, dB_k (reduce over a task's tokens)
 hipError_t lowrank_rows_mfma(const CallCtx& c, const bf16* In, int inner, bf16* Out, const PtrTable& M, bool a_major);
 // `partial`: grad_partial_bytes(c.st, wide) bytes of scratch for calls whose tasks x column blocks

@@ -20,7 +20,7 @@ def mb():
 def test_exports_match_header(mb, header, exports):
     text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(mlora_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(mlora_[a-z0-9_]+)\s*\(", text))
     assert declared == set(getattr(mb, exports))
     for name in declared:
         assert hasattr(mb.lib, name), name
@@ -150,6 +150,45 @@ def test_recompute_entry_points_reject_before_launch(mb):
     bad = _problem(mb, off=(0, 40, 30))
     assert b(ctypes.byref(bad.c), 0x10, 0x11, 0x30, pa, pa, 0, 0x40, 1 << 20, None) == 3
     assert mb.lib.mlora_lora_recompute_workspace_bytes(ctypes.byref(bad.c)) == 0
+
+
+def test_w8_entry_points_reject_before_launch(mb):
+    """The 8-bit-weight calls: p->W is ignored, the workspace also holds the decoded weight, and
+    NULL codes, NULL buffers and a short workspace are reported without touching the GPU."""
+    p = _problem(mb)
+    plain = p.workspace_bytes()
+    ws = p.w8_workspace_bytes()
+    assert ws == plain + (32 * 48 * 2 + 255) // 256 * 256
+    p.c.W = None                      # not needed by the w8 calls ...
+    assert p.w8_workspace_bytes() == ws
+    assert p.validate() == 1          # ... while the plain calls insist on it
+    f = mb.lib.mlora_lora_fwd_w8
+    assert f(ctypes.byref(p.c), None, 0x70, 0x10, 0x20, 0x30, 0x40, ws, None) == 1
+    assert f(ctypes.byref(p.c), 0x60, None, 0x10, 0x20, 0x30, 0x40, ws, None) == 1
+    assert f(ctypes.byref(p.c), 0x60, 0x70, None, 0x20, 0x30, 0x40, ws, None) == 1
+    assert f(ctypes.byref(p.c), 0x60, 0x70, 0x10, 0x20, 0x30, None, ws, None) == 6
+    assert f(ctypes.byref(p.c), 0x60, 0x70, 0x10, 0x20, 0x30, 0x40, ws - 1, None) == 6
+    assert f(ctypes.byref(p.c), 0x60, 0x70, 0x10, 0x20, 0x30, 0x40, plain, None) == 6
+    assert f(None, 0x60, 0x70, 0x10, 0x20, 0x30, 0x40, ws, None) == 1
+    b = mb.lib.mlora_lora_bwd_w8
+    arr = (ctypes.c_void_p * 2)(0x50, 0x60)
+    pa = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    assert b(ctypes.byref(p.c), None, 0x70, 0x10, 0x11, 0x20, 0x30, pa, pa, 0, 0x40, ws, None) == 1
+    assert b(ctypes.byref(p.c), 0x60, 0x70, 0x10, None, 0x20, 0x30, pa, pa, 0, 0x40, ws, None) == 1
+    assert b(ctypes.byref(p.c), 0x60, 0x70, 0x10, 0x11, 0x20, 0x30, None, pa, 0, 0x40, ws, None) == 1
+    assert b(ctypes.byref(p.c), 0x60, 0x70, 0x10, 0x11, 0x20, 0x30, pa, pa, 0, 0x40, ws - 1, None) == 6
+    bad = _problem(mb, off=(0, 40, 30))
+    assert bad.w8_workspace_bytes() == 0
+    assert f(ctypes.byref(bad.c), 0x60, 0x70, 0x10, 0x20, 0x30, 0x40, 1 << 20, None) == 3
+    assert b(ctypes.byref(bad.c), 0x60, 0x70, 0x10, 0x11, 0x20, 0x30, pa, pa, 0, 0x40, 1 << 20, None) == 3
+    empty = _problem(mb, T=0, off=(0, 0, 0))
+    assert f(ctypes.byref(empty.c), 0x60, 0x70, None, None, None, None, 0, None) == 0
+    q, dq = mb.lib.mlora_w8_quantize, mb.lib.mlora_w8_dequantize
+    assert q(None, 0, 8, 8, 0x10, 0x20, None) == 1 and q(0x10, 0, 8, 8, None, 0x20, None) == 1
+    assert q(0x10, 3, 8, 8, 0x20, 0x30, None) == 5
+    assert q(0x10, 0, 0, 8, 0x20, 0x30, None) == 2 and q(0x10, 0, 8, (1 << 22) + 1, 0x20, 0x30, None) == 2
+    assert dq(0x10, None, 0, 8, 8, 0x30, None) == 1 and dq(0x10, 0x20, 0, 8, 8, None, None) == 1
+    assert dq(0x10, 0x20, 9, 8, 8, 0x30, None) == 5 and dq(0x10, 0x20, 1, -1, 8, 0x30, None) == 2
 
 
 def test_group_validation(mb):
