@@ -9,6 +9,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmlora.so")
+# stand-alone characterisation program (csrc/bench/mfma_ceiling.hip), run by bench_mfma_ceiling.py
+CEILING_SRC = os.path.join(CSRC, "bench", "mfma_ceiling.hip")
+CEILING_BIN = os.path.join(HERE, "mfma_ceiling.bin")
 OBJ = os.path.join(HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -47,6 +50,13 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("link failed")
     if verbose:
         print("built", LIB)
+    r = subprocess.run([HIPCC, *[f for f in FLAGS if f != "-fPIC"], CEILING_SRC, "-o", CEILING_BIN],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("hipcc failed on " + CEILING_SRC)
+    if verbose:
+        print("built", CEILING_BIN)
     return LIB
 
 
