@@ -1,18 +1,29 @@
 // Hardware characterisation for the base-product kernel (not a product kernel, not linked into
 // libmlora): what one MI355X sustains on the inner loop of a 256 x 256 x 64 bf16 GEMM tile when
 // the loop's ingredients are added one at a time.  256 blocks of 8 waves (one per CU), wave tile
-// 128 x 64, fp32 accumulators in AccVGPRs, operand values drawn like the benchmark's
-// (activations ~ N(0,1), weights ~ N(0, 0.02^2)): the board runs at its power cap under matrix
-// work, and what it sustains there depends on the data and on everything else that draws power.
+// 128 x 64, fp32 accumulators in AccVGPRs updated in place, the same sub-step schedule as
+// k_gemm_mfma (row fragments double-buffered and read one sub-step ahead, weight fragments
+// re-read in place behind their last use, loads behind the MFMAs of the last sub-step, one
+// barrier per tile) -- so every register that an MFMA reads was loaded at least 12 MFMAs earlier
+// and no level stalls on a dependency the real kernel does not have.
 //
 //   level 0  MFMAs on fragments held in registers
-//   level 1  + every fragment re-read from LDS as the GEMM does (ds_read_b128, one MFMA step ahead)
-//   level 2  + the tile's 64 KiB staged by direct global->LDS loads from an L2-resident matrix
-//   level 3  + the loads follow the GEMM's addresses: an 8 x 4 patch of tiles per XCD over
-//            A [32768, ld] and W [1024, ld], 128 B further along every row per tile
+//   level 1  + every fragment re-read from LDS as the GEMM does (24 ds_read_b128 per wave and tile)
+//   level 2  + the tile's 64 KiB staged by direct global->LDS loads from an L2-resident matrix,
+//            s_waitcnt vmcnt + one barrier per tile
+//   level 3  + the loads follow the GEMM's addresses (an 8 x 4 patch of tiles per XCD over
+//            A [rows, 5120] and W [1024, 5120], 128 B further along every row per tile), with A
+//            small enough (168 MB) to stay in the 256 MB Infinity Cache from pass to pass
+//   level 4  the same with twice the rows of A (336 MB, alternating halves): A streams from HBM
 //
-// Every address is in bounds by construction, every barrier is reached by all waves of a block,
-// and nothing is read back from the staged data: the figures are rates, not results.
+// Each level runs twice: on operand values drawn like the benchmark's (activations ~ N(0,1),
+// weights ~ N(0, 0.02^2)), where the board sits at its power cap, and on all-zero operands,
+// where it does not -- the second column shows what the instruction stream and the memory
+// system allow, the first what the power cap leaves of it.
+//
+// Every address is in bounds by construction (checked again on the host before the launches),
+// every barrier is reached by all waves of a block, and nothing is read back from the staged
+// data: the figures are rates, not results.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -34,100 +45,227 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
     }                                                                                 \
   } while (0)
 
+constexpr int kRowBytes = 10240;            // 5120 bf16 per row
+constexpr int kStepsPerPass = 80;           // 80 x 128 B = one row
+constexpr int kRowsA = 32768, kRowsW = 1024;
+
 __device__ __forceinline__ void load_lds_16B(const void* g, char* lds_wave_base) {
   const unsigned lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds_wave_base;
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds) : "memory", "m0");
 }
+__device__ __forceinline__ void mfma16(f32x4& c, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32(f32x16& c, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
 
-// SHAPE 0: v_mfma_f32_32x32x16_bf16 (4 x 2 fragments, 4 k-steps), 1: v_mfma_f32_16x16x32_bf16
-// (8 x 4 fragments, 2 k-steps); 64 or 32 ... both 8.4 MFLOP per wave-tile step of 64.
-template <int SHAPE, int LEVEL>
+// Level 0 for the 32 x 32 x 16 shape: 4 x 2 fragments, 4 k-steps = 32 MFMAs per wave and tile.
+__global__ __launch_bounds__(512) void k_regs_32x32x16(const bf16* __restrict__ src, float* __restrict__ out, int iters) {
+  __shared__ __attribute__((aligned(1024))) char lds[65536];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < 65536 / 16; i += 512) reinterpret_cast<uint4*>(lds)[i] = reinterpret_cast<const uint4*>(src)[i];
+  __syncthreads();
+  f32x16 acc[4][2];
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 2; ++j)
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  bf16x8 af[4], bfr[2];
+  for (int i = 0; i < 4; ++i) af[i] = *(const bf16x8*)(lds + lane * 16 + ((wave % 4) * 4 + i) * 1024);
+  for (int j = 0; j < 2; ++j) bfr[j] = *(const bf16x8*)(lds + 32768 + lane * 16 + ((wave % 4) * 2 + j) * 1024);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int m = 0; m < 32; ++m) {
+      mfma32(acc[(m / 2) % 4][m % 2], bfr[m % 2], af[(m / 2) % 4]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  float s = 0.f;
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 2; ++j)
+      for (int e = 0; e < 16; ++e) s += acc[i][j][e];
+  out[blockIdx.x * 512 + tid] = s;
+}
+
+// Levels 0..4 for the 16 x 16 x 32 shape (8 x 4 fragments, 2 k-steps = 64 MFMAs per wave and tile).
+template <int LEVEL>
 __global__ __launch_bounds__(512) void k_ceiling(const bf16* __restrict__ src, const char* __restrict__ A,
-                                                 const char* __restrict__ W, float* __restrict__ out, int iters,
-                                                 int ld, int kt) {
-  constexpr int MF = SHAPE == 0 ? 32 : 16;
-  constexpr int FM = 128 / MF, FN = 64 / MF;
-  constexpr int KSTEPS = SHAPE == 0 ? 4 : 2;
-  constexpr int NMF = FM * FN * KSTEPS;     // MFMAs per wave per tile
+                                                 const char* __restrict__ W, float* __restrict__ out, int iters) {
+  constexpr int FM = 8, FN = 4, HM = 4;
   constexpr int NLD = 8;                    // 1 KiB loads per wave per tile (64 KiB per block)
   __shared__ __attribute__((aligned(1024))) char lds[131072];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   for (int i = tid; i < 65536 / 16; i += 512) reinterpret_cast<uint4*>(lds)[i] = reinterpret_cast<const uint4*>(src)[i];
   __syncthreads();
-  {
-    float keep = 0.f;   // makes the compiler place the accumulators in AccVGPRs
-    asm volatile("" : "+a"(keep));
-  }
-  typedef typename std::conditional<SHAPE == 0, f32x16, f32x4>::type accT;
-  constexpr int NE = SHAPE == 0 ? 16 : 4;
-  accT acc[FM][FN];
+  f32x4 acc[FM][FN];
   for (int i = 0; i < FM; ++i)
     for (int j = 0; j < FN; ++j)
-      for (int e = 0; e < NE; ++e) acc[i][j][e] = 0.f;
-  bf16x8 af[FM], bfr[FN];
-  const char* abase = lds + lane * 16 + (wave % 4) * (FM * 1024);          // activations: first 32 KiB
-  const char* bbase = lds + 32768 + lane * 16 + (wave % 4) * (FN * 1024);  // weights: next 32 KiB
-  for (int i = 0; i < FM; ++i) af[i] = *(const bf16x8*)(abase + i * 1024);
-  for (int j = 0; j < FN; ++j) bfr[j] = *(const bf16x8*)(bbase + j * 1024);
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+  // fragment pool: activations in the first 32 KiB (32 pieces of 1 KiB), weights in the next 32 KiB
+  const char* apool = lds + lane * 16;
+  const char* bpool = lds + 32768 + lane * 16;
+  bf16x8 af[2][HM], bfr[FN];
+  for (int i = 0; i < HM; ++i) af[0][i] = *(const bf16x8*)(apool + ((wave % 4) * 8 + i) * 1024);
+  for (int j = 0; j < FN; ++j) bfr[j] = *(const bf16x8*)(bpool + ((wave % 4) * 8 + j) * 1024);
+  if (LEVEL == 0)
+    for (int i = 0; i < HM; ++i) af[1][i] = *(const bf16x8*)(apool + ((wave % 4) * 8 + 4 + i) * 1024);
   char* land = lds + 65536 + wave * NLD * 1024;   // where this wave's loads land (never read)
+
+  // per-lane source addresses of the wave's 8 loads (4 pieces of the A tile, 4 of the W tile;
+  // a piece is 8 rows x 128 B)
   const char* gsrc[NLD];
   const int b = blockIdx.x, x = b % 8, l = b / 8, pm = l % 8, pn = l / 8;
   for (int i = 0; i < NLD; ++i) {
-    const int piece = wave + 8 * (i % 4);          // 1 KiB piece of the operand tile: 8 rows x 128 B
+    const int piece = wave + 8 * (i % 4);
     const int row = 8 * piece + lane / 8, c = lane % 8;
-    if (LEVEL == 3)
-      gsrc[i] = i < 4 ? A + (size_t)((x * 8 + pm) * 256 + row) * ld + c * 16 : W + (size_t)(pn * 256 + row) * ld + c * 16;
-    else
-      gsrc[i] = (i < 4 ? A : W) + (size_t)row * ld + c * 16;
+    int arow = row, wrow = row;                                    // level 2: every block the same 256 + 256 rows
+    if (LEVEL >= 3) { arow = (x * 8 + pm) * 256 + row; wrow = pn * 256 + row; }
+    gsrc[i] = i < 4 ? A + (size_t)arow * kRowBytes + c * 16 : W + (size_t)wrow * kRowBytes + c * 16;
   }
-  const size_t a_pass = LEVEL == 3 ? (size_t)64 * 256 * ld : 0;   // next pass over K: the other 64 row tiles of A
+  // level 2 walks 4 KiB of every row (1 MiB per operand: L2-resident); levels 3, 4 the whole row
+  constexpr int KT = LEVEL == 2 ? 32 : kStepsPerPass;
+  const size_t a_pass = LEVEL == 4 ? (size_t)64 * 256 * kRowBytes : 0;   // odd passes: the other 16384 rows of A
   unsigned koff = 0;
-  int kcount = 0, pass = 0, foff = 0;
-  for (int it = 0; it < iters; ++it) {
-    int ldi = 0;
+  int kcount = 0, pass = 0;
+
+  // sub-step S of a tile: 16 MFMAs on (k-half q = S / 2, row half h = S % 2), weight fragment by weight fragment
+  auto substep = [&](auto S_, int frag_base) {
+    constexpr int S = decltype(S_)::value;
+    constexpr int h = S % 2, nh = (S + 1) % 2;
 #pragma unroll
-    for (int m = 0; m < NMF; ++m) {
-      const int ks = m / (FM * FN), r = m % (FM * FN), i = r / FN, j = r % FN;
-      if constexpr (SHAPE == 0)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-      else
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-      if (LEVEL >= 1 && r < FM + FN) {   // next k-step's fragments, one read behind each MFMA
-        const int o = ((foff + (ks + 1) * 8192) & 16383) & ~1023;
-        if (r < FN) bfr[r] = *(const bf16x8*)(bbase + (o & 8191) + r * 1024);
-        else af[r - FN] = *(const bf16x8*)(abase + (o & 8191) + (r - FN) * 1024);
+    for (int m = 0; m < 16; ++m) {
+      const int j = m / HM, i = m % HM;
+      mfma16(acc[h * HM + i][j], bfr[j], af[h][i]);
+      if (LEVEL >= 1) {
+        // the next sub-step's row fragments behind the first four MFMAs; in the second sub-step of
+        // a k-half, weight fragment j for the next k-half right behind its last MFMA
+        if (m < HM) af[nh][m] = *(const bf16x8*)(apool + ((frag_base + 4 * ((S + 1) % 4) + m) & 31) * 1024);
+        if (h == 1 && i == HM - 1) bfr[j] = *(const bf16x8*)(bpool + ((frag_base + 4 * ((S + 1) % 4) + j + 16) & 31) * 1024);
       }
-      if (LEVEL >= 2 && m >= NMF - NLD) {   // next tile's loads behind the last MFMAs of this one
-        const size_t po = ldi < 4 ? (size_t)(pass & 1) * a_pass : 0;
-        load_lds_16B(gsrc[ldi] + koff + po, land + ldi * 1024);
-        ++ldi;
+      if (LEVEL >= 2 && S == 3 && m >= HM && i != HM - 1) {
+        const int idx = (j - 1) * (HM - 1) + i;
+        if (idx < NLD) {
+          const size_t po = idx < 4 ? (size_t)(pass & 1) * a_pass : 0;
+          load_lds_16B(gsrc[idx] + koff + po, land + idx * 1024);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    foff = (foff + 8192) & 16383;
-    koff += 128;
-    if (++kcount == kt) { kcount = 0; koff = 0; ++pass; }
+  };
+  constexpr std::integral_constant<int, 0> S0{};
+  constexpr std::integral_constant<int, 1> S1{};
+  constexpr std::integral_constant<int, 2> S2{};
+  constexpr std::integral_constant<int, 3> S3{};
+  for (int it = 0; it < iters; ++it) {
+    const int fb = (wave % 4) * 8 + (it & 1) * 2;
+    substep(S0, fb);
+    substep(S1, fb);
+    substep(S2, fb);
     if (LEVEL >= 2) {
-      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // the previous tile's loads have landed
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the loads issued a tile ago have landed
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      __builtin_amdgcn_s_barrier();                      // one barrier per tile, as in the GEMM
+      __builtin_amdgcn_s_barrier();
     }
+    substep(S3, fb);
+    koff += 128;
+    if (++kcount == KT) { kcount = 0; koff = 0; ++pass; }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   float s = (float)(unsigned char)land[lane];
   for (int i = 0; i < FM; ++i)
     for (int j = 0; j < FN; ++j)
-      for (int e = 0; e < NE; ++e) s += acc[i][j][e];
+      for (int e = 0; e < 4; ++e) s += acc[i][j][e];
   out[blockIdx.x * 512 + tid] = s;
 }
 
-typedef void (*kfn)(const bf16*, const char*, const char*, float*, int, int, int);
-struct Variant { const char* mfma; const char* level; kfn f; int ld, kt; };
+// The same levels for a block of 4 waves (one per SIMD), wave tile 128 x 128 = 8 x 8 fragments:
+// a third fewer LDS fragment reads per flop (32 per wave and tile, 128 per block instead of 192).
+// Schedule: a tile is two phases of 64 MFMAs (one per k-half); both operands' fragments are
+// double-buffered by phase (2 x 16 fragments in registers), the 16 reads of the next phase ride
+// behind the first 48 MFMAs of the current one, the tile's 16 loads behind the MFMAs of the
+// second phase, the barrier sits between the phases.
+template <int LEVEL>
+__global__ __launch_bounds__(256) void k_ceiling4(const bf16* __restrict__ src, const char* __restrict__ A,
+                                                  const char* __restrict__ W, float* __restrict__ out, int iters) {
+  constexpr int FM = 8, FN = 8, NLD = 16;
+  __shared__ __attribute__((aligned(1024))) char lds[131072];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  for (int i = tid; i < 65536 / 16; i += 256) reinterpret_cast<uint4*>(lds)[i] = reinterpret_cast<const uint4*>(src)[i];
+  __syncthreads();
+  f32x4 acc[FM][FN];
+  for (int i = 0; i < FM; ++i)
+    for (int j = 0; j < FN; ++j)
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+  const char* apool = lds + lane * 16;
+  const char* bpool = lds + 32768 + lane * 16;
+  bf16x8 fa[2][FM], fb[2][FN];
+  for (int q = 0; q < 2; ++q) {
+    for (int i = 0; i < FM; ++i) fa[q][i] = *(const bf16x8*)(apool + (((wave % 2) * 16 + q * 8 + i) & 31) * 1024);
+    for (int j = 0; j < FN; ++j) fb[q][j] = *(const bf16x8*)(bpool + (((wave / 2) * 16 + q * 8 + j) & 31) * 1024);
+  }
+  char* land = lds + 65536 + wave * NLD * 1024;
+  const char* gsrc[NLD];
+  const int b = blockIdx.x, x = b % 8, l = b / 8, pm = l % 8, pn = l / 8;
+  for (int i = 0; i < NLD; ++i) {
+    const int piece = wave + 4 * (i % 8);                       // 32 pieces of 8 rows per operand tile
+    const int row = 8 * piece + lane / 8, c = lane % 8;
+    int arow = row, wrow = row;
+    if (LEVEL >= 3) { arow = (x * 8 + pm) * 256 + row; wrow = pn * 256 + row; }
+    gsrc[i] = i < 8 ? A + (size_t)arow * kRowBytes + c * 16 : W + (size_t)wrow * kRowBytes + c * 16;
+  }
+  constexpr int KT = LEVEL == 2 ? 32 : kStepsPerPass;
+  const size_t a_pass = LEVEL == 4 ? (size_t)64 * 256 * kRowBytes : 0;
+  unsigned koff = 0;
+  int kcount = 0, pass = 0;
+  auto phase = [&](auto Q_, int frag_base) {
+    constexpr int q = decltype(Q_)::value;
+#pragma unroll
+    for (int m = 0; m < 64; ++m) {
+      const int j = m / FM, i = m % FM;
+      mfma16(acc[i][j], fb[q][j], fa[q][i]);
+      if (LEVEL >= 1 && m % 3 == 0 && m / 3 < 16) {
+        // the other phase's fragments in the order its MFMAs need them: weight fragment 0, the 8 row
+        // fragments, weight fragments 1..7
+        const int n = m / 3;
+        if (n == 0) fb[q ^ 1][0] = *(const bf16x8*)(bpool + ((frag_base + 16) & 31) * 1024);
+        else if (n <= 8) fa[q ^ 1][n - 1] = *(const bf16x8*)(apool + ((frag_base + n) & 31) * 1024);
+        else fb[q ^ 1][n - 8] = *(const bf16x8*)(bpool + ((frag_base + n + 8) & 31) * 1024);
+      }
+      if (LEVEL >= 2 && q == 1 && m % 3 == 1 && m / 3 < NLD) {
+        const int idx = m / 3;
+        const size_t po = idx < 8 ? (size_t)(pass & 1) * a_pass : 0;
+        load_lds_16B(gsrc[idx] + koff + po, land + idx * 1024);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  constexpr std::integral_constant<int, 0> Q0{};
+  constexpr std::integral_constant<int, 1> Q1{};
+  for (int it = 0; it < iters; ++it) {
+    const int fb_ = (wave % 2) * 16 + (it & 1) * 3;
+    phase(Q0, fb_);
+    if (LEVEL >= 2) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+    }
+    phase(Q1, fb_ + 5);
+    koff += 128;
+    if (++kcount == KT) { kcount = 0; koff = 0; ++pass; }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  float s = (float)(unsigned char)land[lane];
+  for (int i = 0; i < FM; ++i)
+    for (int j = 0; j < FN; ++j)
+      for (int e = 0; e < 4; ++e) s += acc[i][j][e];
+  out[blockIdx.x * 256 + tid] = s;
+}
 
 int main(int argc, char** argv) {
   const int iters = argc > 1 ? atoi(argv[1]) : 8000;   // tiles per block
   const int reps = argc > 2 ? atoi(argv[2]) : 4;       // the first repetition is a warm-up
-  std::vector<bf16> h(32768);
+  if (iters < 1 || reps < 2) return 1;
+  std::vector<bf16> h(32768), zeros(32768, (bf16)0.f);
   unsigned x = 12345u;
   auto rnd = [&]() { x = x * 1664525u + 1013904223u; return (x >> 8) * (1.0f / 16777216.0f); };
   for (int i = 0; i < 32768; ++i) {
@@ -138,47 +276,71 @@ int main(int argc, char** argv) {
   bf16* src;
   float* out;
   char *A, *W;
-  const size_t LD = 10240;   // bytes per row: 5120 bf16
-  const size_t abytes = (size_t)32768 * LD + 65536, wbytes = (size_t)1024 * LD + 65536;
+  const size_t abytes = (size_t)kRowsA * kRowBytes, wbytes = (size_t)kRowsW * kRowBytes;
+  // host-side bound check of the kernels' address patterns: the largest row any lane reads is
+  // (7 * 8 + 7) * 256 + 255 = 16383 (+ 16384 on odd passes of level 4) of A and 3 * 256 + 255 of W,
+  // the largest byte within a row 79 * 128 + 7 * 16 + 15
+  {
+    const size_t max_arow = (size_t)(7 * 8 + 7) * 256 + 255 + (size_t)64 * 256, max_wrow = 3 * 256 + 255;
+    const size_t max_col = (size_t)(kStepsPerPass - 1) * 128 + 7 * 16 + 16;
+    if (max_arow * kRowBytes + max_col > abytes || max_wrow * kRowBytes + max_col > wbytes) {
+      printf("address pattern exceeds the buffers\n");
+      return 1;
+    }
+  }
   CK(hipMalloc(&src, 65536));
   CK(hipMalloc(&out, 256 * 512 * 4));
   CK(hipMalloc(&A, abytes));
   CK(hipMalloc(&W, wbytes));
-  CK(hipMemcpy(src, h.data(), 65536, hipMemcpyHostToDevice));
   CK(hipMemset(A, 0x3c, abytes));
   CK(hipMemset(W, 0x3c, wbytes));
-  const std::vector<Variant> vs = {
-      {"32x32x16", "0 registers only", k_ceiling<0, 0>, 4096, 16},
-      {"32x32x16", "1 + LDS fragment reads", k_ceiling<0, 1>, 4096, 16},
-      {"32x32x16", "2 + global->LDS loads, L2-resident", k_ceiling<0, 2>, 4096, 16},
-      {"32x32x16", "3 + GEMM addresses (A 32768 x 5120, W 1024 x 5120)", k_ceiling<0, 3>, 10240, 80},
-      {"16x16x32", "0 registers only", k_ceiling<1, 0>, 4096, 16},
-      {"16x16x32", "1 + LDS fragment reads", k_ceiling<1, 1>, 4096, 16},
-      {"16x16x32", "2 + global->LDS loads, L2-resident", k_ceiling<1, 2>, 4096, 16},
-      {"16x16x32", "3 + GEMM addresses (A 32768 x 5120, W 1024 x 5120)", k_ceiling<1, 3>, 10240, 80},
+  struct Variant { const char* name; int level; };   // level -1: the 32x32x16 register loop
+  const Variant vs[] = {
+      {"32x32x16, registers only", -1},
+      {"16x16x32, 0 registers only", 0},
+      {"16x16x32, 1 + LDS fragment reads", 1},
+      {"16x16x32, 2 + global->LDS loads (L2-resident), barrier", 2},
+      {"16x16x32, 3 + GEMM addresses, A in the Infinity Cache", 3},
+      {"16x16x32, 4 + GEMM addresses, A streamed from HBM", 4},
+      {"4 waves of 128 x 128: 1 + LDS fragment reads", 11},
+      {"4 waves of 128 x 128: 2 + global->LDS loads (L2-resident), barrier", 12},
+      {"4 waves of 128 x 128: 3 + GEMM addresses, A in the Infinity Cache", 13},
+      {"4 waves of 128 x 128: 4 + GEMM addresses, A streamed from HBM", 14},
   };
+  constexpr int NV = sizeof(vs) / sizeof(vs[0]);
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0));
   CK(hipEventCreate(&e1));
   const double flops = 2.0 * 256 * 256 * 64 * (double)iters * 256;
-  std::vector<double> sum(vs.size(), 0);
-  for (int r = 0; r < reps; ++r)
-    for (size_t i = 0; i < vs.size(); ++i) {
-      CK(hipEventRecord(e0));
-      hipLaunchKernelGGL(vs[i].f, dim3(256), dim3(512), 0, 0, src, A, W, out, iters, vs[i].ld, vs[i].kt);
-      CK(hipGetLastError());
-      CK(hipEventRecord(e1));
-      CK(hipEventSynchronize(e1));
-      float ms;
-      CK(hipEventElapsedTime(&ms, e0, e1));
-      if (r > 0) sum[i] += flops / ms / 1e9;
-      printf("rep %d %s level %s: %.1f TFLOP/s\n", r, vs[i].mfma, vs[i].level, flops / ms / 1e9);
-      fflush(stdout);
-    }
-  printf("| MFMA | inner loop | TFLOP/s | share of 2500 |\n|---|---|---|---|\n");
-  for (size_t i = 0; i < vs.size(); ++i) {
-    const double tf = sum[i] / (reps - 1);
-    printf("| %s | %s | %.0f | %.3f |\n", vs[i].mfma, vs[i].level, tf, tf / 2500.0);
+  double tf[2][NV] = {};
+  for (int data = 0; data < 2; ++data) {
+    CK(hipMemcpy(src, data == 0 ? h.data() : zeros.data(), 65536, hipMemcpyHostToDevice));
+    for (int r = 0; r < reps; ++r)
+      for (int i = 0; i < NV; ++i) {
+        CK(hipEventRecord(e0));
+        switch (vs[i].level) {
+          case -1: hipLaunchKernelGGL(k_regs_32x32x16, dim3(256), dim3(512), 0, 0, src, out, iters); break;
+          case 0: hipLaunchKernelGGL(k_ceiling<0>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
+          case 1: hipLaunchKernelGGL(k_ceiling<1>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
+          case 2: hipLaunchKernelGGL(k_ceiling<2>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
+          case 3: hipLaunchKernelGGL(k_ceiling<3>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
+          case 4: hipLaunchKernelGGL(k_ceiling<4>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
+          case 11: hipLaunchKernelGGL(k_ceiling4<1>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
+          case 12: hipLaunchKernelGGL(k_ceiling4<2>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
+          case 13: hipLaunchKernelGGL(k_ceiling4<3>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
+          default: hipLaunchKernelGGL(k_ceiling4<4>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
+        }
+        CK(hipGetLastError());
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        float ms;
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        if (r > 0) tf[data][i] += flops / ms / 1e9 / (reps - 1);
+        printf("%s rep %d %s: %.1f TFLOP/s\n", data == 0 ? "random" : "zeros", r, vs[i].name, flops / ms / 1e9);
+        fflush(stdout);
+      }
   }
+  printf("| inner loop | TFLOP/s, N(0,1) x N(0,0.02^2) operands | share of 2500 | TFLOP/s, all-zero operands |\n|---|---|---|---|\n");
+  for (int i = 0; i < NV; ++i) printf("| %s | %.0f | %.3f | %.0f |\n", vs[i].name, tf[0][i], tf[0][i] / 2500.0, tf[1][i]);
   return 0;
 }
