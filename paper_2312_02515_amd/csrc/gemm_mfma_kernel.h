@@ -339,13 +339,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
 
   // Which of the wave's WM / 32 pieces take part in a tile: all of them in a base tile, the
   // pieces of task k in a LoRA tile of task k (the others' MFMAs are skipped).
+  // `q1`: whether the second half of the tile's 64 contraction indices holds anything -- a LoRA
+  // tile whose remaining ranks are at most 32 (rank 8, 16, 32: most adapters) runs the MFMAs of
+  // its first half only (the other half of the staged operands is zeros).
   struct FragOn {
     bool on[WM / 32];
+    bool q1;
   };
-  auto frags_of = [&](int k) {  // k < 0: base tile
+  auto frags_of = [&](const LoraTile& t, bool base) {
     FragOn f;
 #pragma unroll
-    for (int i = 0; i < WM / 32; ++i) f.on[i] = k < 0 || frag_task(wm * (WM / 32) + i) == k;
+    for (int i = 0; i < WM / 32; ++i) f.on[i] = base || frag_task(wm * (WM / 32) + i) == t.k;
+    f.q1 = base || (int)ga.rank[t.sg][t.k < 0 ? 0 : t.k] - t.q0 > 32;
     return f;
   };
 
@@ -372,7 +377,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     for (int m = 0; m < NMF; ++m) {
       const int j = m / HM, i = m % HM;
       bool on = true;
-      if constexpr (!std::is_same_v<std::decay_t<decltype(fo)>, std::true_type>) on = fo.on[(h * HM + i) / 2];
+      if constexpr (!std::is_same_v<std::decay_t<decltype(fo)>, std::true_type>) on = fo.on[(h * HM + i) / 2] && (q == 0 || fo.q1);
       if (on) mfma_16x16x32(acc[h * HM + i][j], bfr[j], af[h][i]);
       if (rd && m < HM) read_a(rsa, nq, nh, m, af[nh]);
       if (rd && h == 1 && i == HM - 1) read_b(rsb, nq, j);
@@ -444,7 +449,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       tile(stage1, yes, yes, base_ctx(v + 3), yes);
     }
     // the last base tiles and the LoRA tiles
-    auto frags_at = [&](int u) { return frags_of(u < KT ? -1 : find_lora(u - KT).k); };
+    auto frags_at = [&](int u) { return u < KT ? frags_of(LoraTile{0, -1, 0}, true) : frags_of(find_lora(u - KT), false); };
     for (; v < VT; v += 2) {
       tile(stage0, v + 1 < VT, v + 2 < VT, v + 2 < VT ? ctx_of(v + 2) : none, frags_at(v));
       if (v + 1 < VT) tile(stage1, v + 2 < VT, v + 3 < VT, v + 3 < VT ? ctx_of(v + 3) : none, frags_at(v + 1));
