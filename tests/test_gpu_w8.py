@@ -204,3 +204,51 @@ def test_w8_full_size_sampled(mb):
     inp_hat = copy.copy(inp)
     inp_hat.W = w8.dequantize_w8(ref_q, ref_c)        # float64, exact
     check_sampled(inp_hat, out, TOL[torch.bfloat16], rows, grad_adapters=[0, 7, 15], label="w8 q_proj full size")
+
+
+def test_w8_hip_graph_capture_and_replay(mb):
+    """The 8-bit-weight calls allocate nothing either (decoder and operator kernels only, no
+    memset): a captured forward + backward pair replays to the eager result bit for bit, with
+    eager work between the replays, and follows new codes written into the same buffers."""
+    T, h, d, tokens, ranks, lead = MFMA_SMALL_CASES[2]
+    inp = _case(T, h, d, tokens, ranks, lead, torch.bfloat16, seed=91)
+    Wq, c = mb.mlora_w8_quantize(inp.W)
+    prob = mb.Problem(T, h, d, None, inp.seg_offsets, inp.ranks, inp.scalings, inp.A, inp.B,
+                      dtype=torch.bfloat16, device=DEV)
+    saved, ws = prob.alloc_saved(), prob.alloc_w8_workspace()
+    Y = torch.empty((T, d), dtype=torch.bfloat16, device=DEV)
+    dX = torch.empty((T, h), dtype=torch.bfloat16, device=DEV)
+    dA, dB = prob.alloc_grads()
+
+    def call(stream=None):
+        mb.mlora_lora_fwd_w8(prob, Wq, c, inp.X, Y, saved, ws, stream)
+        mb.mlora_lora_bwd_w8(prob, Wq, c, inp.X, inp.dY, saved, dX, dA, dB, False, ws, stream)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in [Y, dX] + dA + dB]
+
+    call()
+    eager = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        call(torch.cuda.current_stream())
+    for rep in range(3):
+        for t in [Y, dX] + dA + dB:
+            t.fill_(float("nan"))
+        ws.fill_(0x5A)                     # the decoded weight is rebuilt by every call
+        torch.cuda.synchronize()
+        graph.replay()
+        for a, b in zip(eager, snapshot()):
+            assert torch.equal(a, b), f"replay {rep}"
+    Wq2, c2 = mb.mlora_w8_quantize((inp.W.float() * 1.5).to(torch.bfloat16).flip(0).contiguous())
+    Wq.copy_(Wq2)
+    c.copy_(c2)
+    call()
+    eager2 = snapshot()
+    graph.replay()
+    for a, b in zip(eager2, snapshot()):
+        assert torch.equal(a, b)
+    assert not torch.equal(eager[0], eager2[0])
