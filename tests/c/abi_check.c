@@ -56,6 +56,20 @@ int main(void) {
     EXPECT(mlora_lora_group_validate(ps, MLORA_MAX_GROUP + 1) == MLORA_ERR_SHAPE);
     EXPECT(mlora_lora_group_workspace_bytes(ps, 2) == 2 * mlora_lora_workspace_bytes(&p));
   }
+  /* the 8-bit-weight calls: p.W is not looked at; argument checks come before any GPU work */
+  p.W = NULL;
+  EXPECT(mlora_lora_w8_workspace_bytes(&p) > mlora_lora_saved_bytes(&p));
+  EXPECT(mlora_lora_fwd_w8(&p, NULL, (const float*)0x70, (void*)0x10, (void*)0x20, (void*)0x30, (void*)0x40, 1u << 20,
+                           NULL) == MLORA_ERR_NULL);
+  EXPECT(mlora_lora_fwd_w8(&p, (const int8_t*)0x60, (const float*)0x70, (void*)0x10, (void*)0x20, (void*)0x30,
+                           (void*)0x40, 16, NULL) == MLORA_ERR_WORKSPACE);
+  EXPECT(mlora_w8_quantize((const void*)0x10, 7, 8, 8, (int8_t*)0x20, (float*)0x30, NULL) == MLORA_ERR_DTYPE);
+  EXPECT(mlora_w8_dequantize((const int8_t*)0x10, (const float*)0x20, MLORA_BF16, 0, 8, (void*)0x30, NULL) ==
+         MLORA_ERR_SHAPE);
+  EXPECT(mlora_lora_kernel_path(&p) == -1);
+  p.W = (const void*)0x5000;
+  EXPECT(mlora_lora_kernel_path(&p) == 3);   /* h, d not multiples of 64: the generic kernels */
+  EXPECT(mlora_lora_bwd_static(&p, (void*)0x10, NULL, (void*)0x20, (void*)0x30, NULL, NULL, 0, NULL) == MLORA_ERR_NULL);
   EXPECT(strlen(mlora_status_string(MLORA_ERR_WORKSPACE)) > 0);
   printf(fails ? "abi_check: %d failure(s)\n" : "abi_check: ok\n", fails);
   return fails ? 1 : 0;
