@@ -12,8 +12,8 @@
 // 16x16x32 shape on the same data.
 //
 // Tile 256 x 256 x 64, WAVES_M x WAVES_N waves (2 x 4: wave tile WM x WN = 128 x 64), fp32
-// accumulators in AccVGPRs, LDS tiles filled by direct global->LDS loads (16 B per lane) into a
-// double buffer.  A wave-wide direct load fills 1 KiB of contiguous LDS, so the bank-conflict
+// accumulators in AccVGPRs, LDS tiles filled by direct global->LDS loads (16 B per lane) into
+// three stages for A and two for Bm.  A wave-wide direct load fills 1 KiB of contiguous LDS, so the bank-conflict
 // swizzle is applied by choosing which global 16-byte chunk each lane fetches:
 //   * K-contiguous tiles (A, and Bm when !NN): 256 rows x 128 B; chunk c of row r sits at chunk
 //     position c ^ ((r >> 1) & 7); a fragment (16 rows x 32 contraction indices) is one
@@ -33,9 +33,16 @@
 // its half tile and is re-read in place right behind its last MFMA, a sub-step before its next
 // use.  At most one memory instruction rides behind each MFMA:
 //   sub-steps 0..2 of tile kt: MFMAs | LDS reads of the next sub-step's fragments
-//   s_waitcnt vmcnt(0), lgkmcnt(0); barrier  (tile kt+1 visible; every wave holds its last
-//                                             fragments of tile kt in registers: kt's stage is free)
-//   sub-step 3: MFMAs | LDS reads of tile kt+1's first fragments | the direct loads of tile kt+2
+//   s_waitcnt vmcnt(4), lgkmcnt(0); barrier  (tile kt+1 visible -- the 4 loads still in flight are
+//                                             A's of tile kt+2; every wave holds its last fragments
+//                                             of tile kt in registers: kt's stages are free)
+//   sub-step 3: MFMAs | LDS reads of tile kt+1's first fragments | the direct loads of Bm's tile
+//               kt+2, then of A's tile kt+3
+// A is loaded two tiles ahead because its rows come from HBM, once per launch: with one tile of
+// lead the blocks that share a row strip stalled together on every cold line (the time lost grew
+// linearly with the rate at which A is read from HBM, at every shape measured).  Bm, the weight,
+// is read from the Infinity Cache and keeps one tile of lead; 3 + 2 stages of 32 KiB are all of
+// the CU's 160 KiB of LDS, which is why the block's piece table lives in a register.
 //
 // Rows: the grid tiles a virtual row axis on which every row range of the call (the rows before
 // the first task, each task's rows, the rows after the last task) is padded to a multiple of 32.
@@ -109,11 +116,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   constexpr int PER_TILE = 2 * LPW;
   static_assert(WM == 128, "the sub-steps halve a 128-row wave tile");
 
+  // Three stages for the A side, two for the Bm side: all 160 KiB of the CU's LDS.  The rows of
+  // A come from HBM (every element once per launch, cold), the weight from the Infinity Cache; a
+  // cold line takes longer than the one contraction tile a two-stage ring gives it, and every
+  // block that shares the strip waits for it together.  With the third stage the A loads run two
+  // tiles ahead of their use, the Bm loads one.
   __shared__ __attribute__((aligned(1024))) char sA0[TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) char sA1[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sA2[TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) char sB0[TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) char sB1[TILE_BYTES];
-  char* const sA[2] = {sA0, sA1};
+  char* const sA[3] = {sA0, sA1, sA2};
   char* const sB[2] = {sB0, sB1};
 
   // block -> tile.  Tiles are taken in a grouped order (8 row tiles x all column tiles per group,
@@ -150,10 +163,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   // the last row: such a piece re-reads row M-1 and stores nothing) and task (-1 = rows of no
   // task).  Range s of the call is [b_s, b_{s+1}) with b_0 = 0, b_{1+k} = off[k], b_{K+2} = M;
   // task k owns range 1 + k.
+  // The table lives in one vector register (the stages leave no LDS for it): every wave works it
+  // out for itself, lane 8 c + f holding column c (0: first row, 1: rows, 2: task) of piece f.
+  // Every use looks up a wave-uniform piece, so an entry is read with v_readlane.
   constexpr int NFR = BM / 32;
-  __shared__ int s_frow[NFR], s_fn[NFR], s_ftask[NFR];
-  if (tid < NFR) {
-    const int v0 = tm * BM + 32 * tid;
+  int v_tab;
+  {
+    const int v0 = tm * BM + 32 * (lane & (NFR - 1));
     int vstart = 0, prev = 0, frow = M - 1, fn = 0, ftask = -1;
     for (int r = 0; r < ga.K + 2; ++r) {
       const int b1 = r <= ga.K ? ga.off[r] : M;
@@ -167,14 +183,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       vstart += vlen;
       prev = b1;
     }
-    s_frow[tid] = frow;
-    s_fn[tid] = fn;
-    s_ftask[tid] = ftask;
+    const int col = lane / NFR;
+    v_tab = col == 0 ? frow : (col == 1 ? fn : ftask);
   }
-  __syncthreads();
-  auto frag_row = [&](int f) { return __builtin_amdgcn_readfirstlane(s_frow[f]); };
-  auto frag_n = [&](int f) { return __builtin_amdgcn_readfirstlane(s_fn[f]); };
-  auto frag_task = [&](int f) { return __builtin_amdgcn_readfirstlane(s_ftask[f]); };
+  auto tab = [&](int c, int f) { return __builtin_amdgcn_readlane(v_tab, __builtin_amdgcn_readfirstlane(NFR * c + f)); };
+  auto frag_row = [&](int f) { return tab(0, f); };
+  auto frag_n = [&](int f) { return tab(1, f); };
+  auto frag_task = [&](int f) { return tab(2, f); };
   const int row0 = frag_row(0);  // the block's lowest real row
   // real row behind row rl (0..255) of the block's tile; the 8 rows of one wave-wide load lie in
   // one piece, so f is wave-uniform there
@@ -264,7 +279,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   // (B_k or A_k), fetched into the same LDS layouts by the same direct loads two tiles ahead --
   // so the LoRA term costs ceil(r_k / 64) more tiles on the same accumulators and no exposed
   // load latency.  The pieces of one task are consecutive, so the block's tasks are the runs of
-  // s_ftask.
+  // the task column of the piece table.
   struct LoraTile {
     int sg, k, q0;
   };
@@ -366,8 +381,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   // the steady-state loop, so that it compiles to straight-line code, and plain bools in the few
   // tiles around it; `fo` is std::true_type there (base tiles: every piece) and a FragOn in
   // the tiles that may be LoRA tiles.
-  auto substep = [&](auto S_, auto rd, const char* rsa, const char* rsb, auto ld, const LoadCtx& lc, char* lsa, char* lsb,
-                     const auto& fo) {
+  auto substep = [&](auto S_, auto rd, const char* rsa, const char* rsb, auto ldb, const LoadCtx& lcb, char* lsb, auto lda,
+                     const LoadCtx& lca, char* lsa, const auto& fo) {
     constexpr int S = decltype(S_)::value;
     constexpr int q = S / 2, h = S % 2;
     constexpr int NS_ = (S + 1) % 4;                 // the sub-step whose row fragments are read now
@@ -382,8 +397,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       if (rd && m < HM) read_a(rsa, nq, nh, m, af[nh]);
       if (rd && h == 1 && i == HM - 1) read_b(rsb, nq, j);
       if (S == 3 && m >= HM && i != HM - 1) {
+        // the Bm side first: the next barrier waits for it and lets the A loads behind it fly on
         const int idx = (j - 1) * (HM - 1) + i;
-        if (ld && idx < PER_TILE) issue_one(lc, idx, lsa, lsb);
+        if (ldb && idx < LPW) issue_one(lcb, LPW + idx, nullptr, lsb);
+        if (lda && idx >= LPW && idx < PER_TILE) issue_one(lca, idx - LPW, lsa, nullptr);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -396,27 +413,32 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   constexpr std::integral_constant<int, 3> S3{};
   const LoadCtx none{false, nullptr, nullptr, LoraTile{0, -1, 0}};
 
-  // the tile in stage s: sub-steps 0..2, barrier, sub-step 3 with the reads of the next tile's
-  // first fragments (if rd) and the loads of the tile after that, `lc`, into stage s (if ld)
-  auto tile = [&](auto stage, auto rd, auto ld, const LoadCtx& lc, const auto& fo) {
-    constexpr int s = decltype(stage)::value;
-    substep(S0, yes, sA[s], sB[s], no, none, nullptr, nullptr, fo);
-    substep(S1, yes, sA[s], sB[s], no, none, nullptr, nullptr, fo);
-    substep(S2, yes, sA[s], sB[s], no, none, nullptr, nullptr, fo);
+  // A tile whose operands sit in (ca, cb): sub-steps 0..2, barrier, sub-step 3 with the reads of
+  // the next tile's first fragments from (na, nb) (if rd), the Bm loads of the tile after that,
+  // `lcb`, into cb (if ldb) and the A loads of the tile after that one, `lca`, into ca (if lda).
+  // `abehind`: whether A loads were issued behind the Bm loads the barrier waits for (the
+  // previous tile's lda) -- vector loads return in order, so the wait leaves exactly those LPW
+  // loads in flight.
+  auto tile = [&](char* ca, char* cb, const char* na, const char* nb, auto rd, auto ldb, const LoadCtx& lcb, auto lda,
+                  const LoadCtx& lca, auto abehind, const auto& fo) {
+    substep(S0, yes, ca, cb, no, none, nullptr, no, none, nullptr, fo);
+    substep(S1, yes, ca, cb, no, none, nullptr, no, none, nullptr, fo);
+    substep(S2, yes, ca, cb, no, none, nullptr, no, none, nullptr, fo);
     // the next tile has landed (this wave's part), every fragment of this tile is in registers
     // (the weight fragments of this half tile stay in use until sub-step 3 re-reads them)
-    wait_vmcnt<0>();
+    if (abehind)
+      wait_vmcnt<LPW>();
+    else
+      wait_vmcnt<0>();
     wait_lds();
     __builtin_amdgcn_s_barrier();
-    substep(S3, rd, sA[s ^ 1], sB[s ^ 1], ld, lc, sA[s], sB[s], fo);
+    substep(S3, rd, na, nb, ldb, lcb, cb, lda, lca, ca, fo);
   };
-  constexpr std::integral_constant<int, 0> stage0{};
-  constexpr std::integral_constant<int, 1> stage1{};
 
-  // ---- main contraction loop (unrolled by the two stages so that stage addresses are constants).
-  // Operand pairs run one after the other.  When a pair's last tile has passed its barrier every
-  // wave holds that tile's last fragments in registers, so both stages are free for the next
-  // pair's first two tiles.
+  // ---- main contraction loop.  Tile v of a pass uses A stage v % 3 and Bm stage v % 2; the steady
+  // state is unrolled by six so that stage addresses are constants.  Operand pairs run one after
+  // the other.  When a pair's last tile has passed its barrier every wave holds that tile's last
+  // fragments in registers, so all stages are free for the next pair's first tiles.
   for (int sg = 0; sg < NSEG; ++sg) {
     set_operands(ga.A[sg], ga.Bm[sg], ga.Kd[sg]);
     const int KT = ga.Kd[sg] / BK;
@@ -425,14 +447,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
       if (v < KT) return base_ctx(v);
       return LoadCtx{true, nullptr, nullptr, find_lora(v - KT)};
     };
-    auto issue_whole = [&](const LoadCtx& lc, char* sa, char* sb) {
+    auto issue_a = [&](const LoadCtx& lc, char* sa) {
 #pragma unroll
-      for (int idx = 0; idx < PER_TILE; ++idx) issue_one(lc, idx, sa, sb);
+      for (int idx = 0; idx < LPW; ++idx) issue_one(lc, idx, sa, nullptr);
     };
-    issue_whole(base_ctx(0), sA[0], sB[0]);
-    if (VT > 1) {
-      issue_whole(ctx_of(1), sA[1], sB[1]);
-      wait_vmcnt<PER_TILE>();
+    auto issue_b = [&](const LoadCtx& lc, char* sb) {
+#pragma unroll
+      for (int idx = 0; idx < LPW; ++idx) issue_one(lc, LPW + idx, nullptr, sb);
+    };
+    // tiles 0 and 1 whole and the A side of tile 2; the first reads need tile 0
+    issue_a(base_ctx(0), sA[0]);
+    issue_b(base_ctx(0), sB[0]);
+    if (VT > 2) {
+      issue_a(ctx_of(1), sA[1]);
+      issue_b(ctx_of(1), sB[1]);
+      issue_a(ctx_of(2), sA[2]);
+      wait_vmcnt<3 * LPW>();
+    } else if (VT > 1) {
+      issue_a(ctx_of(1), sA[1]);
+      issue_b(ctx_of(1), sB[1]);
+      wait_vmcnt<2 * LPW>();
     } else {
       wait_vmcnt<0>();
     }
@@ -442,17 +476,28 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
 #pragma unroll
     for (int i = 0; i < HM; ++i) read_a(sA[0], 0, 0, i, af[0]);
     __builtin_amdgcn_sched_barrier(0);
-    // steady state, two base tiles per trip: both have a successor to read and a base tile to load
+    // steady state, six base tiles per trip: each has a successor to read, a base tile two ahead
+    // for its Bm loads and one three ahead for its A loads
     int v = 0;
-    for (; v + 3 < KT; v += 2) {
-      tile(stage0, yes, yes, base_ctx(v + 2), yes);
-      tile(stage1, yes, yes, base_ctx(v + 3), yes);
+    for (; v + 8 < KT; v += 6) {
+      tile(sA[0], sB[0], sA[1], sB[1], yes, yes, base_ctx(v + 2), yes, base_ctx(v + 3), yes, yes);
+      tile(sA[1], sB[1], sA[2], sB[0], yes, yes, base_ctx(v + 3), yes, base_ctx(v + 4), yes, yes);
+      tile(sA[2], sB[0], sA[0], sB[1], yes, yes, base_ctx(v + 4), yes, base_ctx(v + 5), yes, yes);
+      tile(sA[0], sB[1], sA[1], sB[0], yes, yes, base_ctx(v + 5), yes, base_ctx(v + 6), yes, yes);
+      tile(sA[1], sB[0], sA[2], sB[1], yes, yes, base_ctx(v + 6), yes, base_ctx(v + 7), yes, yes);
+      tile(sA[2], sB[1], sA[0], sB[0], yes, yes, base_ctx(v + 7), yes, base_ctx(v + 8), yes, yes);
     }
+    // (v is a multiple of 6 here.)  The up to seven base tiles left that still have all of the
+    // above: the same straight-line code, with the stage addresses in registers
+    auto stage_a = [&](int u) { return u % 3 == 0 ? sA0 : (u % 3 == 1 ? sA1 : sA2); };
+    auto stage_b = [&](int u) { return u % 2 == 0 ? sB0 : sB1; };
+    for (; v + 3 < KT; ++v)
+      tile(stage_a(v), stage_b(v), stage_a(v + 1), stage_b(v + 1), yes, yes, base_ctx(v + 2), yes, base_ctx(v + 3), yes, yes);
     // the last base tiles and the LoRA tiles
     auto frags_at = [&](int u) { return u < KT ? frags_of(LoraTile{0, -1, 0}, true) : frags_of(find_lora(u - KT), false); };
-    for (; v < VT; v += 2) {
-      tile(stage0, v + 1 < VT, v + 2 < VT, v + 2 < VT ? ctx_of(v + 2) : none, frags_at(v));
-      if (v + 1 < VT) tile(stage1, v + 2 < VT, v + 3 < VT, v + 3 < VT ? ctx_of(v + 3) : none, frags_at(v + 1));
+    for (; v < VT; ++v) {
+      tile(stage_a(v), stage_b(v), stage_a(v + 1), stage_b(v + 1), v + 1 < VT, v + 2 < VT, v + 2 < VT ? ctx_of(v + 2) : none,
+           v + 3 < VT, v + 3 < VT ? ctx_of(v + 3) : none, v + 2 < VT, frags_at(v));
     }
   }  // operand pairs
 
@@ -489,11 +534,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
     const int r = ORPI * it + lane / OCH, cp = lane % OCH;
     const int c = cp ^ oswz(r);
     const uint4 v = *(const uint4*)(ep + r * OROWB + cp * 16);
-    const int f = (wm * WM + r) >> 5, o = r & 31;  // the row's piece of the block (WM is a multiple of 32)
-    const int grow = s_frow[f] + o, gcol = col0 + wn * WN + c * 8;
+    // the row's piece of the block (WM is a multiple of 32; the rows of one store share a piece)
+    const int f = (wm * WM + ORPI * it) >> 5, o = r & 31;
+    const int grow = frag_row(f) + o, gcol = col0 + wn * WN + c * 8;
     // non-temporal: the output is not read again by this launch, so it should not displace the
     // operand strips in the L2 / Infinity Cache (measured +0.7 % on the whole forward + backward)
-    if (o < s_fn[f] && gcol < N)
+    if (o < frag_n(f) && gcol < N)
       __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4*)(C + (size_t)grow * N + gcol));
   }
 }
