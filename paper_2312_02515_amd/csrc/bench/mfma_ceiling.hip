@@ -14,7 +14,13 @@
 //   level 3  + the loads follow the GEMM's addresses (an 8 x 4 patch of tiles per XCD over
 //            A [rows, 5120] and W [1024, 5120], 128 B further along every row per tile), with A
 //            small enough (168 MB) to stay in the 256 MB Infinity Cache from pass to pass
-//   level 4  the same with twice the rows of A (336 MB, alternating halves): A streams from HBM
+//   level 4  the same with twice the rows of A (336 MB, alternating halves): A streams from HBM.
+//            Every XCD walks row strips of its own here, so A leaves HBM at five times the rate of
+//            the GEMM, where the XCDs that work on one row group share its strips through the
+//            Infinity Cache: the level bounds the effect from above
+//   level 5  level 4 with k_gemm_mfma's load order and wait: the weight's loads first, then A's,
+//            and the wait in front of the barrier leaves A's four loads in flight -- A has two
+//            tiles of lead over its use (the kernel's three A stages), the weight one
 //
 // Each level runs twice: on operand values drawn like the benchmark's (activations ~ N(0,1),
 // weights ~ N(0, 0.02^2)), where the board sits at its power cap, and on all-zero operands,
@@ -87,7 +93,7 @@ __global__ __launch_bounds__(512) void k_regs_32x32x16(const bf16* __restrict__ 
   out[blockIdx.x * 512 + tid] = s;
 }
 
-// Levels 0..4 for the 16 x 16 x 32 shape (8 x 4 fragments, 2 k-steps = 64 MFMAs per wave and tile).
+// Levels 0..5 for the 16 x 16 x 32 shape (8 x 4 fragments, 2 k-steps = 64 MFMAs per wave and tile).
 template <int LEVEL>
 __global__ __launch_bounds__(512) void k_ceiling(const bf16* __restrict__ src, const char* __restrict__ A,
                                                  const char* __restrict__ W, float* __restrict__ out, int iters) {
@@ -124,7 +130,7 @@ __global__ __launch_bounds__(512) void k_ceiling(const bf16* __restrict__ src, c
   }
   // level 2 walks 4 KiB of every row (1 MiB per operand: L2-resident); levels 3, 4 the whole row
   constexpr int KT = LEVEL == 2 ? 32 : kStepsPerPass;
-  const size_t a_pass = LEVEL == 4 ? (size_t)64 * 256 * kRowBytes : 0;   // odd passes: the other 16384 rows of A
+  const size_t a_pass = LEVEL >= 4 ? (size_t)64 * 256 * kRowBytes : 0;   // odd passes: the other 16384 rows of A
   unsigned koff = 0;
   int kcount = 0, pass = 0;
 
@@ -145,8 +151,9 @@ __global__ __launch_bounds__(512) void k_ceiling(const bf16* __restrict__ src, c
       if (LEVEL >= 2 && S == 3 && m >= HM && i != HM - 1) {
         const int idx = (j - 1) * (HM - 1) + i;
         if (idx < NLD) {
-          const size_t po = idx < 4 ? (size_t)(pass & 1) * a_pass : 0;
-          load_lds_16B(gsrc[idx] + koff + po, land + idx * 1024);
+          const int g = LEVEL >= 5 ? (idx + 4) % NLD : idx;   // level 5: the weight's four loads first
+          const size_t po = g < 4 ? (size_t)(pass & 1) * a_pass : 0;
+          load_lds_16B(gsrc[g] + koff + po, land + g * 1024);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -162,7 +169,10 @@ __global__ __launch_bounds__(512) void k_ceiling(const bf16* __restrict__ src, c
     substep(S1, fb);
     substep(S2, fb);
     if (LEVEL >= 2) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the loads issued a tile ago have landed
+      if (LEVEL >= 5)
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // all but A's loads of a tile ago have landed
+      else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the loads issued a tile ago have landed
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
     }
@@ -278,7 +288,7 @@ int main(int argc, char** argv) {
   char *A, *W;
   const size_t abytes = (size_t)kRowsA * kRowBytes, wbytes = (size_t)kRowsW * kRowBytes;
   // host-side bound check of the kernels' address patterns: the largest row any lane reads is
-  // (7 * 8 + 7) * 256 + 255 = 16383 (+ 16384 on odd passes of level 4) of A and 3 * 256 + 255 of W,
+  // (7 * 8 + 7) * 256 + 255 = 16383 (+ 16384 on odd passes of levels 4 and 5) of A and 3 * 256 + 255 of W,
   // the largest byte within a row 79 * 128 + 7 * 16 + 15
   {
     const size_t max_arow = (size_t)(7 * 8 + 7) * 256 + 255 + (size_t)64 * 256, max_wrow = 3 * 256 + 255;
@@ -302,6 +312,7 @@ int main(int argc, char** argv) {
       {"16x16x32, 2 + global->LDS loads (L2-resident), barrier", 2},
       {"16x16x32, 3 + GEMM addresses, A in the Infinity Cache", 3},
       {"16x16x32, 4 + GEMM addresses, A streamed from HBM", 4},
+      {"16x16x32, 5 = 4 with A's loads two tiles ahead of their use", 5},
       {"4 waves of 128 x 128: 1 + LDS fragment reads", 11},
       {"4 waves of 128 x 128: 2 + global->LDS loads (L2-resident), barrier", 12},
       {"4 waves of 128 x 128: 3 + GEMM addresses, A in the Infinity Cache", 13},
@@ -325,6 +336,7 @@ int main(int argc, char** argv) {
           case 2: hipLaunchKernelGGL(k_ceiling<2>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
           case 3: hipLaunchKernelGGL(k_ceiling<3>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
           case 4: hipLaunchKernelGGL(k_ceiling<4>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
+          case 5: hipLaunchKernelGGL(k_ceiling<5>, dim3(256), dim3(512), 0, 0, src, A, W, out, iters); break;
           case 11: hipLaunchKernelGGL(k_ceiling4<1>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
           case 12: hipLaunchKernelGGL(k_ceiling4<2>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
           case 13: hipLaunchKernelGGL(k_ceiling4<3>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
