@@ -193,7 +193,8 @@ __global__ __launch_bounds__(512) void k_ceiling(const bf16* __restrict__ src, c
 // Schedule: a tile is two phases of 64 MFMAs (one per k-half); both operands' fragments are
 // double-buffered by phase (2 x 16 fragments in registers), the 16 reads of the next phase ride
 // behind the first 48 MFMAs of the current one, the tile's 16 loads behind the MFMAs of the
-// second phase, the barrier sits between the phases.
+// second phase, the barrier sits between the phases.  (Level 5 as above: the weight's eight
+// loads first, vmcnt(8) in front of the barrier.)
 template <int LEVEL>
 __global__ __launch_bounds__(256) void k_ceiling4(const bf16* __restrict__ src, const char* __restrict__ A,
                                                   const char* __restrict__ W, float* __restrict__ out, int iters) {
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(256) void k_ceiling4(const bf16* __restrict__ src, 
     gsrc[i] = i < 8 ? A + (size_t)arow * kRowBytes + c * 16 : W + (size_t)wrow * kRowBytes + c * 16;
   }
   constexpr int KT = LEVEL == 2 ? 32 : kStepsPerPass;
-  const size_t a_pass = LEVEL == 4 ? (size_t)64 * 256 * kRowBytes : 0;
+  const size_t a_pass = LEVEL >= 4 ? (size_t)64 * 256 * kRowBytes : 0;
   unsigned koff = 0;
   int kcount = 0, pass = 0;
   auto phase = [&](auto Q_, int frag_base) {
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(256) void k_ceiling4(const bf16* __restrict__ src, 
         else fb[q ^ 1][n - 8] = *(const bf16x8*)(bpool + ((frag_base + n + 8) & 31) * 1024);
       }
       if (LEVEL >= 2 && q == 1 && m % 3 == 1 && m / 3 < NLD) {
-        const int idx = m / 3;
+        const int idx = LEVEL >= 5 ? (m / 3 + 8) % NLD : m / 3;   // level 5: the weight's eight loads first
         const size_t po = idx < 8 ? (size_t)(pass & 1) * a_pass : 0;
         load_lds_16B(gsrc[idx] + koff + po, land + idx * 1024);
       }
@@ -255,7 +256,10 @@ __global__ __launch_bounds__(256) void k_ceiling4(const bf16* __restrict__ src, 
     const int fb_ = (wave % 2) * 16 + (it & 1) * 3;
     phase(Q0, fb_);
     if (LEVEL >= 2) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (LEVEL >= 5)
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // A's loads of a tile ago stay in flight
+      else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
     }
@@ -317,6 +321,7 @@ int main(int argc, char** argv) {
       {"4 waves of 128 x 128: 2 + global->LDS loads (L2-resident), barrier", 12},
       {"4 waves of 128 x 128: 3 + GEMM addresses, A in the Infinity Cache", 13},
       {"4 waves of 128 x 128: 4 + GEMM addresses, A streamed from HBM", 14},
+      {"4 waves of 128 x 128: 5 = 4 with A's loads two tiles ahead of their use", 15},
   };
   constexpr int NV = sizeof(vs) / sizeof(vs[0]);
   hipEvent_t e0, e1;
@@ -340,7 +345,8 @@ int main(int argc, char** argv) {
           case 11: hipLaunchKernelGGL(k_ceiling4<1>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
           case 12: hipLaunchKernelGGL(k_ceiling4<2>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
           case 13: hipLaunchKernelGGL(k_ceiling4<3>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
-          default: hipLaunchKernelGGL(k_ceiling4<4>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
+          case 14: hipLaunchKernelGGL(k_ceiling4<4>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
+          default: hipLaunchKernelGGL(k_ceiling4<5>, dim3(256), dim3(256), 0, 0, src, A, W, out, iters); break;
         }
         CK(hipGetLastError());
         CK(hipEventRecord(e1));
