@@ -47,6 +47,25 @@ def test_small_shapes(dtype, case):
     check_full(inp, out, TOL[dtype], label=f"{case}")
 
 
+@pytest.mark.parametrize("case", [
+    # T, h, d, tokens, ranks, lead -- contraction tiles of 64 (base + LoRA) forward / backward:
+    (300, 64, 64, [], [], 0),               # 1 / 1   no adapter, one tile: nothing to prefetch
+    (300, 64, 128, [300], [8], 0),          # 2 / 3   one base tile and one LoRA tile
+    (300, 128, 64, [100, 150], [64, 16], 20),  # 3-4 / 2-3  two tasks in one row tile
+    (300, 64, 64, [300], [128], 0),         # 3 / 3   rank 128: two LoRA tiles behind one base tile
+    (520, 192, 128, [260, 260], [32, 128], 0),  # 4-5 / 3-4, two row tiles
+    (300, 256, 192, [200], [16], 50),       # 5 / 4   just below the depth where the loop proper starts
+])
+def test_short_contractions(case):
+    """The base-product kernel keeps three tiles of A and two of the weight in flight; with
+    fewer tiles than that in all (small h or d, with and without LoRA tiles behind them) its
+    prologue and its last tiles take their short forms."""
+    T, h, d, tokens, ranks, lead = case
+    inp = _inputs(T, h, d, tokens, ranks, torch.bfloat16, lead=lead, seed=23, scal=[1.0 + 0.5 * i for i in range(len(ranks))])
+    out = run_hip(inp)
+    check_full(inp, out, TOL[torch.bfloat16], label=f"short {case}")
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("case", LORA_TERM_CASES)
 def test_lora_term_alone(dtype, case):
