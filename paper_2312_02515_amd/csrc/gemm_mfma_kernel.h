@@ -136,7 +136,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void k_gemm_mfma(const GemmA
   // 8 (l / 32) + x: the blocks resident on one XCD share their strips in that XCD's L2 (hit rate
   // 79 %, the share an 8 x 4 patch allows), and the eight XCDs work on eight neighbouring chunks,
   // i.e. on one or two row groups of A at a time.  (Giving each XCD a contiguous eighth of the
-  // order instead, eight row groups at a time, measured the same.)  Other patch shapes: 4 x 8
+  // order instead, eight row groups at a time: level on benchmark-like data, 2-10 % slower when
+  // the weight is 141 MB, because every XCD then walks all of it on its own.)  Other patch shapes: 4 x 8
   // misses more where the column tiles are no multiple of 8, 16 x 2 is 9 % slower.
   // The tiles beyond the last full round of 256 are taken in block order.
   const int total = tiles_m * tiles_n;
